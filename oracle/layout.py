@@ -1,0 +1,191 @@
+"""Tile-level keep rule and sparse layout (oracle side; test infrastructure).
+
+What is computed (Sec. 4.1).  Each head owns a list of frame-distance groups.
+A group is `(max_dt, window_a, window_b)`; a window is `(rh, rw)`, radii in
+tiles along the height and width axes, and is absent when a radius is
+negative.  For a query tile (qt, qh, qw) and a key tile (kt, kh, kw):
+
+  * dt = |kt - qt| selects the first group with dt <= max_dt (groups have
+    strictly increasing max_dt).  No such group: the key tile is dropped.
+  * the key tile is kept iff it lies in window a or in window b, a window
+    being the query-centred box |kh - qh| <= rh and |kw - qw| <= rw
+    (Eq. 1 is one such box; Eq. 2 is the union of two; a box at least as
+    large as the tile grid is the global pattern of Sec. 3.2).  Boxes are
+    clipped by the grid, never re-centred.
+  * text tiles are kept by every query tile, and a text query tile keeps
+    every tile.
+
+Readings taken where the paper is silent: radii in tile units, absolute
+distance between tile-frame indices, ascending tile ids inside a row.
+
+Three independent formulations live here so that they can be checked against
+each other: `keep_pair` (the rule on one pair), `kept_tiles` (enumeration of
+the two clipped boxes per key frame) and `row_count_closed_form`.
+"""
+import numpy as np
+
+from .geometry import Geometry
+
+
+def window_present(win):
+    return win[0] >= 0 and win[1] >= 0
+
+
+def check_head(head):
+    """Validate one head's group list; returns it as a tuple of plain tuples."""
+    out = []
+    last = -1
+    for grp in head:
+        max_dt, a, b = grp
+        if max_dt <= last:
+            raise ValueError("max_dt must be non-negative and strictly increasing")
+        last = max_dt
+        out.append((int(max_dt), (int(a[0]), int(a[1])), (int(b[0]), int(b[1]))))
+    return tuple(out)
+
+
+def group_of(head, dt):
+    """First group whose max_dt covers the tile-frame distance dt, or None."""
+    for grp in head:
+        if dt <= grp[0]:
+            return grp
+    return None
+
+
+def keep_pair(geom: Geometry, head, q_tile, k_tile):
+    """The keep rule evaluated on a single (query tile, key tile) pair."""
+    if q_tile >= geom.n_vid or k_tile >= geom.n_vid:
+        return True  # text rows keep everything; text columns are always kept
+    qt, qh, qw = geom.tile_coords(q_tile)
+    kt, kh, kw = geom.tile_coords(k_tile)
+    grp = group_of(head, abs(kt - qt))
+    if grp is None:
+        return False
+    for win in (grp[1], grp[2]):
+        if window_present(win) and abs(kh - qh) <= win[0] and abs(kw - qw) <= win[1]:
+            return True
+    return False
+
+
+def keep_mask_bruteforce(geom: Geometry, heads):
+    """bool[num_heads, n, n] from the pair rule; a triple loop, tiny grids only."""
+    mask = np.zeros((len(heads), geom.n, geom.n), dtype=bool)
+    for h, head in enumerate(heads):
+        head = check_head(head)
+        for q in range(geom.n):
+            for k in range(geom.n):
+                mask[h, q, k] = keep_pair(geom, head, q, k)
+    return mask
+
+
+def _clipped_box(center, radius, length):
+    """Inclusive index range of |i - center| <= radius inside [0, length)."""
+    return max(center - radius, 0), min(center + radius, length - 1)
+
+
+def kept_tiles(geom: Geometry, head, q_tile):
+    """Ascending int32 array of key tiles kept by `q_tile` under `head`.
+
+    Second formulation: for each key tile-frame, list the tiles of the two
+    clipped boxes and take their union.
+    """
+    if q_tile >= geom.n_vid:
+        return np.arange(geom.n, dtype=np.int32)
+    head = check_head(head)
+    qt, qh, qw = geom.tile_coords(q_tile)
+    kept = []
+    for kt in range(geom.nT):
+        grp = group_of(head, abs(kt - qt))
+        if grp is None:
+            continue
+        frame = set()
+        for win in (grp[1], grp[2]):
+            if not window_present(win):
+                continue
+            h0, h1 = _clipped_box(qh, win[0], geom.nH)
+            w0, w1 = _clipped_box(qw, win[1], geom.nW)
+            for kh in range(h0, h1 + 1):
+                for kw in range(w0, w1 + 1):
+                    frame.add(geom.tile_id(kt, kh, kw))
+        kept.extend(sorted(frame))
+    kept.extend(range(geom.n_vid, geom.n))
+    return np.asarray(kept, dtype=np.int32)
+
+
+def build_csr(geom: Geometry, heads):
+    """Per head: (row_ptr int64[n+1], col_idx int32[nnz]) with ascending columns."""
+    out = []
+    for head in heads:
+        rows = [kept_tiles(geom, head, q) for q in range(geom.n)]
+        row_ptr = np.zeros(geom.n + 1, dtype=np.int64)
+        row_ptr[1:] = np.cumsum([len(r) for r in rows])
+        col_idx = np.concatenate(rows).astype(np.int32) if rows else np.zeros(0, np.int32)
+        out.append((row_ptr, col_idx))
+    return out
+
+
+def _count_1d(center, radius, length):
+    lo, hi = _clipped_box(center, radius, length)
+    return hi - lo + 1
+
+
+def _box_count(geom, qh, qw, win):
+    if not window_present(win):
+        return 0
+    return _count_1d(qh, win[0], geom.nH) * _count_1d(qw, win[1], geom.nW)
+
+
+def row_count_closed_form(geom: Geometry, head, q_tile):
+    """Number of kept key tiles of a row by inclusion-exclusion on the two boxes.
+
+    Both boxes share the centre, so their intersection is the box with the
+    smaller radius on each axis (absent when either window is absent).
+    """
+    if q_tile >= geom.n_vid:
+        return geom.n
+    head = check_head(head)
+    qt, qh, qw = geom.tile_coords(q_tile)
+    total = geom.n_txt
+    for kt in range(geom.nT):
+        grp = group_of(head, abs(kt - qt))
+        if grp is None:
+            continue
+        a, b = grp[1], grp[2]
+        both = (min(a[0], b[0]), min(a[1], b[1])) if window_present(a) and window_present(b) else (-1, -1)
+        total += _box_count(geom, qh, qw, a) + _box_count(geom, qh, qw, b) - _box_count(geom, qh, qw, both)
+    return total
+
+
+def row_counts(geom: Geometry, heads):
+    """int64[num_heads, n] of closed-form row counts."""
+    out = np.zeros((len(heads), geom.n), dtype=np.int64)
+    for h, head in enumerate(heads):
+        for q in range(geom.n):
+            out[h, q] = row_count_closed_form(geom, head, q)
+    return out
+
+
+def work_order(counts):
+    """Order in which (head, query tile) rows are handed to the device.
+
+    Rows with the most kept tiles go first so that long rows do not land at
+    the tail of the launch; ties keep ascending (head, tile) order.  `counts`
+    is int[num_heads, n]; the result is int32[num_heads * n] of flat row ids
+    head * n + tile.  (Not in the paper: a scheduling choice of this build.)
+    """
+    flat = np.asarray(counts).reshape(-1)
+    return np.argsort(-flat, kind="stable").astype(np.int32)
+
+
+def sparsity(geom: Geometry, heads):
+    """Fraction of dropped tile pairs over num_heads * n^2 (padded grid, text included)."""
+    kept = int(row_counts(geom, heads).sum())
+    return 1.0 - kept / (len(heads) * geom.n * geom.n)
+
+
+def mask_similarity(mask_a, mask_b):
+    """Sim(M_A, M_B) of Eq. 3: |A and B| / |A or B| for two binary masks."""
+    a = np.asarray(mask_a, dtype=bool)
+    b = np.asarray(mask_b, dtype=bool)
+    union = np.logical_or(a, b).sum()
+    return 1.0 if union == 0 else float(np.logical_and(a, b).sum()) / float(union)

@@ -1,0 +1,173 @@
+"""Pins for the oracle's keep rule, CSR builder, row counts and work order.
+
+None of these touch the HIP library.  Each test checks the oracle against
+something it does not itself define: hand-worked tile sets, the pair rule by
+brute force, inclusion-exclusion counts, special cases with known answers.
+"""
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle.geometry import Geometry
+from oracle import layout as L
+from workloads import get_workload
+
+ABSENT = (-1, -1)
+
+
+def _geom(wl):
+    return Geometry(wl.T, wl.H, wl.W, *wl.tile, wl.n_text)
+
+
+def test_hand_worked_3x3_single_frame():
+    # one frame, 3x3 tiles (ids row-major):  0 1 2 / 3 4 5 / 6 7 8
+    g = Geometry(1, 3, 3, 1, 1, 1)
+    local1 = [(0, (1, 1), ABSENT)]
+    assert L.kept_tiles(g, local1, 4).tolist() == [0, 1, 2, 3, 4, 5, 6, 7, 8]
+    assert L.kept_tiles(g, local1, 0).tolist() == [0, 1, 3, 4]          # clipped, not re-centred
+    assert L.kept_tiles(g, local1, 5).tolist() == [1, 2, 4, 5, 7, 8]
+    cross0 = [(0, (0, 2), (2, 0))]                                      # full row + full column
+    assert L.kept_tiles(g, cross0, 4).tolist() == [1, 3, 4, 5, 7]
+    assert L.kept_tiles(g, cross0, 0).tolist() == [0, 1, 2, 3, 6]
+    assert L.kept_tiles(g, cross0, 8).tolist() == [2, 5, 6, 7, 8]
+    wide_only = [(0, (0, 1), ABSENT)]                                   # rh=0, rw=1: same row, +-1 column
+    assert L.kept_tiles(g, wide_only, 4).tolist() == [3, 4, 5]          # an rh/rw swap would give [1,4,7]
+
+
+def test_hand_worked_frame_groups():
+    # 4 frames of 1x2 tiles: ids 2*t + w
+    g = Geometry(4, 1, 2, 1, 1, 1)
+    head = [(0, (0, 1), ABSENT), (2, (0, 0), ABSENT)]   # same frame: both tiles; |dt| in 1..2: own column; dt 3: dropped
+    assert L.kept_tiles(g, head, 0).tolist() == [0, 1, 2, 4]
+    assert L.kept_tiles(g, head, 3).tolist() == [1, 2, 3, 5, 7]
+    assert L.kept_tiles(g, head, 7).tolist() == [3, 5, 6, 7]
+    # a group with both windows absent expresses "skip nearby frames"
+    far = [(0, (0, 0), ABSENT), (1, ABSENT, ABSENT), (3, (0, 1), ABSENT)]
+    assert L.kept_tiles(g, far, 0).tolist() == [0, 4, 5, 6, 7]
+
+
+def test_text_tiles_always_kept_and_text_rows_dense():
+    g = Geometry(2, 2, 2, 1, 2, 2, n_text=8)            # 2 video tiles of 4 tokens + 2 text tiles
+    head = [(0, (0, 0), ABSENT)]
+    assert g.n == 4 and g.n_vid == 2
+    assert L.kept_tiles(g, head, 0).tolist() == [0, 2, 3]
+    assert L.kept_tiles(g, head, 1).tolist() == [1, 2, 3]
+    assert L.kept_tiles(g, head, 2).tolist() == [0, 1, 2, 3]
+    assert L.kept_tiles(g, head, 3).tolist() == [0, 1, 2, 3]
+
+
+def test_config1_printed_rows_and_nnz():
+    wl = get_workload("cfg1")
+    g = _geom(wl)
+    assert (g.nT, g.nH, g.nW, g.B, g.n) == (4, 2, 2, 16, 16)
+    assert L.kept_tiles(g, wl.heads[0], 0).tolist() == list(range(8))
+    assert L.kept_tiles(g, wl.heads[1], 0).tolist() == [0, 1, 2, 4, 5, 6, 8, 9, 10, 12, 13, 14]
+    assert L.kept_tiles(g, wl.heads[1], 5).tolist() == [0, 1, 3, 4, 5, 7, 8, 9, 11, 12, 13, 15]
+    csr = L.build_csr(g, wl.heads)
+    assert [int(rp[-1]) for rp, _ in csr] == [160, 192]
+    assert abs(L.sparsity(g, wl.heads) - 0.3125) < 1e-12
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_small_configs_bruteforce_equals_builder(name):
+    wl = get_workload(name)
+    g = _geom(wl)
+    mask = L.keep_mask_bruteforce(g, wl.heads)
+    csr = L.build_csr(g, wl.heads)
+    counts = L.row_counts(g, wl.heads)
+    for h, (row_ptr, col_idx) in enumerate(csr):
+        assert int(row_ptr[-1]) == wl.expected_nnz[h]
+        for q in range(g.n):
+            cols = col_idx[row_ptr[q]:row_ptr[q + 1]]
+            assert np.array_equal(cols, np.nonzero(mask[h, q])[0])
+            assert counts[h, q] == len(cols)
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4-S50", "cfg4-S65", "cfg4-S80", "cfg5"])
+def test_large_configs_closed_form_nnz_matches_table(name):
+    wl = get_workload(name)
+    g = _geom(wl)
+    counts = L.row_counts(g, wl.heads)
+    assert tuple(int(c) for c in counts.sum(axis=1)) == wl.expected_nnz
+    # a few rows enumerated in full, against the pair rule
+    rng = np.random.default_rng(7)
+    for h in rng.choice(wl.num_heads, 3, replace=False):
+        for q in list(rng.choice(g.n, 3, replace=False)) + [0, g.n - 1]:
+            cols = L.kept_tiles(g, wl.heads[h], int(q))
+            assert len(cols) == counts[h, q]
+            brute = [k for k in range(g.n) if L.keep_pair(g, L.check_head(wl.heads[h]), int(q), k)]
+            assert cols.tolist() == brute
+
+
+def test_padded_shapes_of_configs():
+    shapes = {"cfg2": (128, 8192), "cfg3": (1260, 80640), "cfg4-S65": (1022, 130816), "cfg5": (1920, 245760)}
+    for name, (n, n_pad) in shapes.items():
+        g = _geom(get_workload(name))
+        assert (g.n, g.N_pad) == (n, n_pad)
+
+
+def test_full_window_keeps_everything_and_identity_keeps_self():
+    g = Geometry(3, 5, 7, 1, 2, 3, n_text=0)
+    full = [(g.nT - 1, (g.nH - 1, g.nW - 1), ABSENT)]
+    ident = [(0, (0, 0), ABSENT)]
+    for q in range(g.n):
+        assert L.kept_tiles(g, full, q).tolist() == list(range(g.n))
+        assert L.kept_tiles(g, ident, q).tolist() == [q]
+    assert L.sparsity(g, [full]) == 0.0
+
+
+def test_invalid_heads_rejected():
+    with pytest.raises(ValueError):
+        L.check_head([(2, (0, 0), ABSENT), (2, (1, 1), ABSENT)])
+    with pytest.raises(ValueError):
+        L.check_head([(3, (0, 0), ABSENT), (1, (1, 1), ABSENT)])
+    with pytest.raises(ValueError):
+        L.check_head([(-1, (0, 0), ABSENT)])
+
+
+_win = st.tuples(st.integers(-1, 4), st.integers(-1, 4))
+
+
+@st.composite
+def _cases(draw):
+    tt, th, tw = draw(st.integers(1, 2)), draw(st.integers(1, 3)), draw(st.integers(1, 3))
+    T, H, W = draw(st.integers(1, 5)), draw(st.integers(1, 7)), draw(st.integers(1, 7))
+    n_txt = draw(st.integers(0, 2))
+    g = Geometry(T, H, W, tt, th, tw, n_text=n_txt * tt * th * tw)
+    n_groups = draw(st.integers(0, 3))
+    dts = sorted(draw(st.sets(st.integers(0, 5), min_size=n_groups, max_size=n_groups)))
+    head = [(dt, draw(_win), draw(_win)) for dt in dts]
+    return g, head
+
+
+@settings(max_examples=120, deadline=None)
+@given(_cases())
+def test_three_formulations_agree(case):
+    g, head = case
+    mask = L.keep_mask_bruteforce(g, [head])[0]
+    for q in range(g.n):
+        cols = L.kept_tiles(g, head, q)
+        assert np.array_equal(cols, np.nonzero(mask[q])[0])
+        assert L.row_count_closed_form(g, head, q) == len(cols)
+        assert np.all(np.diff(cols) > 0)
+
+
+def test_work_order_is_descending_count_with_stable_ties():
+    rng = np.random.default_rng(3)
+    counts = rng.integers(0, 6, size=(5, 37))
+    order = L.work_order(counts)
+    flat = counts.reshape(-1)
+    ref = np.lexsort((np.arange(flat.size), -flat))
+    assert np.array_equal(order, ref)
+    assert np.all(np.diff(flat[order]) <= 0)
+    assert sorted(order.tolist()) == list(range(flat.size))
+
+
+def test_mask_similarity_closed_forms():
+    a = np.zeros((4, 4), bool)
+    b = np.zeros((4, 4), bool)
+    a[:2] = True
+    b[1:3] = True
+    assert L.mask_similarity(a, a) == 1.0
+    assert L.mask_similarity(a, ~a) == 0.0
+    assert L.mask_similarity(a, b) == pytest.approx(4 / 12)
