@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the Compact Attention hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic, HBM-resident
+inputs: tile-order permutation of Q, K and V, the block-sparse attention
+forward, and the inverse permutation of the output.  The layout (CSR of kept
+tiles) is built once before timing, as the method precomputes it offline.
+
+Prints one JSON line: whole-step throughput in effective TFLOP/s (FLOPs of the
+kept tile pairs / step time) with the attention kernel's own time, its
+fraction of the bf16 MFMA roofline, the speed-up over the same kernel with the
+full mask, and the fp64 oracle timed on the host cores for context.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4-S65")
+    ap.add_argument("--dense-calls", type=int, default=3, help="timed calls of the dense kernel (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle leg (0 = skip)")
+    ap.add_argument("--sweep", action="store_true", help="also time the forward kernel on the other cfg4 sparsities")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, geom, q, k, v, budget_s):
+    """The oracle, as it stands, on a bounded sample of query tiles of the same workload."""
+    import numpy as np
+    from oracle import attention as OA
+    from oracle import layout as OL
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    rng = np.random.default_rng(2508)
+    tok_tile, _ = geom.token_tile_and_slot()
+    pairs = 0
+    tiles = 0
+    heads_used = set()
+    t0 = time.perf_counter()
+    cache = {}
+    while time.perf_counter() - t0 < budget_s:
+        h = int(rng.integers(wl.num_heads))
+        if h not in cache:
+            cache.clear()
+            cache[h] = tuple(t[0, h].cpu().double().numpy() for t in (q, k, v))
+        q_tile = int(rng.integers(geom.n))
+        OA.attention_tile(geom, wl.heads[h], q_tile, *cache[h], token_tile=tok_tile)
+        pairs += OL.row_count_closed_form(geom, wl.heads[h], q_tile)
+        tiles += 1
+        heads_used.add(h)
+    dt = time.perf_counter() - t0
+    flops = pairs * 4.0 * geom.B * geom.B * wl.head_dim
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{tiles} random (head, query tile) rows of {wl.name} ({pairs} tile pairs) in {dt:.1f} s, "
+                  "fp64 numpy incl. host copies; FLOPs counted as for the GPU (4*B^2*D per kept tile pair)",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no collective); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2508_12969_amd as ca
+    from oracle.geometry import Geometry
+    from workloads import get_workload, make_qkv
+
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    wl = get_workload(args.workload)
+    geom = Geometry(wl.T, wl.H, wl.W, *wl.tile, wl.n_text)
+
+    def layout_of(w):
+        return ca.compact_attn_build_layout(w.T, w.H, w.W, w.tile, w.n_text, w.batch, w.num_heads, w.head_dim, w.dtype, w.heads)
+
+    t0 = time.perf_counter()
+    lay = layout_of(wl)
+    ca.compact_attn_layout_upload(lay)
+    layout_build_s = time.perf_counter() - t0
+    q, k, v = make_qkv(wl, dev)
+    shape_p = lay.shape(True)
+    qp, kp, vp, op = (torch.empty(shape_p, dtype=q.dtype, device=dev) for _ in range(4))
+    out = torch.empty_like(q)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    n_ev = args.steps
+    e_fwd = [(ev(), ev()) for _ in range(n_ev)]
+    e_perm = [(ev(), ev()) for _ in range(n_ev)]
+
+    def step(i=None):
+        if i is not None:
+            e_perm[i][0].record()
+        ca.compact_attn_permute(q, lay, out=qp)
+        ca.compact_attn_permute(k, lay, out=kp)
+        ca.compact_attn_permute(v, lay, out=vp)
+        if i is not None:
+            e_perm[i][1].record()
+            e_fwd[i][0].record()
+        ca.compact_attn_forward(qp, kp, vp, lay, out=op)
+        if i is not None:
+            e_fwd[i][1].record()
+        ca.compact_attn_permute(op, lay, inverse=True, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    fwd_ms = sorted(a.elapsed_time(b) for a, b in e_fwd)
+    perm_ms = sorted(a.elapsed_time(b) for a, b in e_perm)
+    fwd_avg = sum(fwd_ms) / len(fwd_ms)
+    fwd_med = fwd_ms[len(fwd_ms) // 2]
+    perm3_avg = sum(perm_ms) / len(perm_ms)
+
+    B, D = geom.B, wl.head_dim
+    flops = lay.nnz_total * wl.batch * 4.0 * B * B * D
+    dense_flops = wl.num_heads * wl.batch * geom.n * geom.n * 4.0 * B * B * D
+    kept = lay.nnz_total / (wl.num_heads * geom.n * geom.n)
+    esz = 2 if wl.dtype == "bf16" else 4
+    perm_bytes = 3 * wl.batch * wl.num_heads * (geom.N_real + geom.N_pad) * D * esz
+
+    dense_ms = None
+    if args.dense_calls > 0:
+        ca.compact_attn_dense(qp, kp, vp, lay, out=op)
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(args.dense_calls):
+            a, b = ev(), ev()
+            a.record()
+            ca.compact_attn_dense(qp, kp, vp, lay, out=op)
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        dense_ms = sorted(ts)[len(ts) // 2]
+
+    sweep = {}
+    if args.sweep:
+        for name in ("cfg4-S50", "cfg4-S65", "cfg4-S80"):
+            w2 = get_workload(name)
+            l2 = layout_of(w2)
+            for _ in range(2):
+                ca.compact_attn_forward(qp, kp, vp, l2, out=op)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(5):
+                a, b = ev(), ev()
+                a.record()
+                ca.compact_attn_forward(qp, kp, vp, l2, out=op)
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            ms = sorted(ts)[len(ts) // 2]
+            f2 = l2.nnz_total * 4.0 * B * B * D
+            sweep[name] = {"ms": ms, "tflops": f2 / ms / 1e9, "kept": l2.nnz_total / (w2.num_heads * geom.n ** 2),
+                           "speedup_vs_dense": (dense_ms / ms) if dense_ms else None}
+            l2.free()
+
+    cpu = cpu_baseline(wl, geom, q, k, v, args.cpu_seconds) if args.cpu_seconds > 0 else None
+
+    rec = {
+        "metric": "sparse attention hot path, effective TFLOP/s on kept tiles (permute q,k,v + sparse forward + inverse permute)",
+        "value": flops / ms_per_step / 1e9,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={wl.T} H={wl.H} W={wl.W} +{wl.n_text} text, tile {wl.tile}, "
+                               f"{wl.num_heads} heads, D={D}, batch {wl.batch}",
+                   "n_tiles": geom.n, "tokens_padded": geom.N_pad, "kept_tile_fraction": kept,
+                   "layout_build_s": layout_build_s},
+        "attn": {"ms_per_call_avg": fwd_avg, "ms_per_call_median": fwd_med, "tflops": flops / fwd_avg / 1e9,
+                 "pct_bf16_mfma_peak": 100.0 * flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
+                 "dense_ms": dense_ms, "dense_tflops": (dense_flops / dense_ms / 1e9) if dense_ms else None,
+                 "speedup_vs_dense": (dense_ms / fwd_med) if dense_ms else None, "ideal_speedup": 1.0 / kept},
+        "permute": {"ms_q_k_v": perm3_avg, "gbps": perm_bytes / perm3_avg / 1e6, "pct_hbm_peak": perm_bytes / perm3_avg / 1e6 / 8000 * 100},
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": flops / fwd_avg / 1e9,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    if sweep:
+        rec["sweep"] = sweep
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

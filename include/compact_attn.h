@@ -1,0 +1,149 @@
+/*
+ * compact_attn.h -- C ABI of the Compact Attention block-sparse forward for MI355X (gfx950).
+ *
+ * The library computes softmax attention over a T x H x W grid of video tokens
+ * (plus optional trailing text tokens) in which every head only attends to a
+ * per-head set of space-time tiles.  The kept set follows Sec. 4.1 of the paper:
+ * frames are grouped by their distance from the query's frame, and inside each
+ * group the spatial mask is the union of two query-centred windows (Eq. 1 is one
+ * window, Eq. 2 the union of two, a window as large as the grid is the global
+ * pattern of Sec. 3.2).  The mask is built once, offline (Sec. 3.3), and the
+ * attention pass visits only kept tiles with an online softmax (Appendix D).
+ *
+ * Conventions common to every entry point
+ *   - Plain C, no exceptions; every function that can fail returns a ca_status
+ *     (0 = success, negative = failure) and records a message readable through
+ *     compact_attn_last_error() on the calling thread.
+ *   - "device pointer" = memory of the current HIP device, owned by the caller,
+ *     16-byte aligned.  "host pointer" = ordinary process memory.
+ *   - Tensors are contiguous [batch, num_heads, N, head_dim], element type
+ *     ca_problem.dtype.  N = N_real (natural order) or N_pad (tile order), see below.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
+ *     calls enqueue work on it and return without synchronising.
+ *   - Failures detected on the host leave all outputs untouched.
+ *
+ * Tile arithmetic (Sec. 4.1, space-time tiles; Sec. 3.1 / Appendix D, tile-order flattening)
+ *   tile = tt x th x tw tokens, B = tt*th*tw; tile grid nT = ceil(T/tt), nH = ceil(H/th),
+ *   nW = ceil(W/tw); n_vid = nT*nH*nW video tiles followed by n_txt = n_text/B text tiles;
+ *   n = n_vid + n_txt; N_real = T*H*W + n_text; N_pad = n*B.
+ *   Natural order: token (t,y,x) at (t*H + y)*W + x, text tokens after the video tokens.
+ *   Tile order: token (t,y,x) at tile*B + slot with tile = ((t/tt)*nH + y/th)*nW + x/tw and
+ *   slot = ((t%tt)*th + y%th)*tw + x%tw; text token j at n_vid*B + j.  Slots of a tile that
+ *   fall outside the grid are padding: zero on input, never attended, zero on output.
+ */
+#ifndef COMPACT_ATTN_H
+#define COMPACT_ATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CA_OK = 0,
+  CA_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, malformed head description, misalignment */
+  CA_ERR_UNSUPPORTED = -2, /* valid request the device kernels do not cover (see compact_attn_forward)   */
+  CA_ERR_ALLOC = -3,       /* host or device allocation failed                                          */
+  CA_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed; message carries the HIP text  */
+} ca_status;
+
+typedef enum { CA_F32 = 0, CA_BF16 = 1 } ca_dtype;
+
+/* One axis-aligned, query-centred window in tile units: key tile (kh,kw) is inside iff
+ * |kh-qh| <= rh and |kw-qw| <= rw (Eq. 1).  A negative radius marks the window absent. */
+typedef struct {
+  int32_t rh, rw;
+} ca_window;
+
+/* One frame-distance group (Sec. 4.1, frame-group-wise patterns): applies to key tiles whose
+ * tile-frame distance |kt-qt| is <= max_dt and larger than the previous group's max_dt.
+ * Kept iff inside window a or window b (Sec. 4.1, dual attention windows; Eq. 2). */
+typedef struct {
+  int32_t max_dt;
+  ca_window a, b;
+} ca_group;
+
+/* One head: up to CA_MAX_GROUPS groups, max_dt non-negative and strictly increasing.
+ * Key tiles farther than the last group's max_dt are dropped.  num_groups = 0 keeps only text tiles. */
+#define CA_MAX_GROUPS 8
+typedef struct {
+  int32_t num_groups;
+  const ca_group* groups; /* host pointer, read during compact_attn_build_layout only */
+} ca_head;
+
+typedef struct {
+  int32_t T, H, W;    /* video token grid                                      */
+  int32_t tt, th, tw; /* tile shape                                            */
+  int32_t n_text;     /* trailing text tokens, a multiple of B (0 = none)      */
+  int32_t batch, num_heads, head_dim;
+  int32_t dtype; /* ca_dtype                                                    */
+  float scale;   /* softmax scale; <= 0 selects head_dim^-1/2                  */
+} ca_problem;
+
+typedef struct ca_layout ca_layout; /* opaque; immutable once built; may be shared by threads */
+
+/* Build the sparse layout (Sec. 4.1; Sec. 3.3: masks are precomputed offline per head).
+ *   problem  host pointer.  heads  host pointer to problem->num_heads descriptions.
+ *   *out     receives a new layout owned by the caller (release with compact_attn_free_layout).
+ * For every head and query tile the layout stores the ascending list of kept key-tile ids (CSR).
+ * A text query tile keeps every tile; every query tile keeps all text tiles.  It also stores
+ * the launch order of the (head, query tile) rows: descending kept count, ties by ascending
+ * (head, tile).  Host-only work: no HIP call is made, so it also runs on a machine without a GPU.
+ * Errors: CA_ERR_INVALID_ARG (null, non-positive dims, n_text not a multiple of B, bad groups),
+ * CA_ERR_ALLOC. */
+int compact_attn_build_layout(const ca_problem* problem, const ca_head* heads, ca_layout** out);
+
+/* Sizes of a layout; any output pointer may be NULL. */
+int compact_attn_layout_info(const ca_layout* layout, int64_t* n_tiles, int64_t* tokens_per_tile,
+                             int64_t* n_tokens_real, int64_t* n_tokens_padded, int64_t* nnz_total);
+
+/* Host views of one head's CSR, owned by the layout and valid until it is freed:
+ *   *row_ptr -> int64[n+1] offsets into *col_idx, relative to this head;
+ *   *col_idx -> int32[(*row_ptr)[n]] kept key-tile ids, ascending inside each row. */
+int compact_attn_layout_csr(const ca_layout* layout, int32_t head, const int64_t** row_ptr,
+                            const int32_t** col_idx);
+
+/* Host view of the launch order: int32[num_heads*n] of row ids head*n + query_tile. */
+int compact_attn_layout_order(const ca_layout* layout, const int32_t** order);
+
+/* Copy the layout's device-side tables (CSR, order, padding masks) to the current HIP device.
+ * Synchronous; idempotent.  The compute calls below do it on first use if it was not called.
+ * Errors: CA_ERR_ALLOC, CA_ERR_HIP. */
+int compact_attn_layout_upload(ca_layout* layout);
+
+/* Release a layout and its device tables (NULL is ignored).  The caller must make sure no
+ * enqueued work still reads it. */
+void compact_attn_free_layout(ca_layout* layout);
+
+/* Tile-order flattening (Sec. 3.1, Appendix D) and its inverse; device pointers.
+ *   inverse = 0: src [batch, heads, N_real, D] natural order -> dst [batch, heads, N_pad, D]
+ *                tile order; padding slots of dst are written as zero.
+ *   inverse = 1: src [.., N_pad, D] tile order -> dst [.., N_real, D] natural order.
+ * src and dst must not overlap.  Bit-exact copy of the elements. */
+int compact_attn_permute(const void* src, void* dst, ca_layout* layout, int32_t inverse, void* stream);
+
+/* Sparse attention forward (Appendix D: block-wise pass with online softmax over kept tiles).
+ *   q, k, v, out: device pointers, [batch, heads, N_pad, D] in tile order; padding slots of
+ *   k and v are ignored, padding rows of out are written as zero.  out must not alias q/k/v.
+ * For each query tile i of each head:  out_i = softmax(scale * Q_i K_J^T) V_J, J = real tokens of
+ * the kept key tiles.  A row whose kept set holds no real key yields zeros.
+ * bf16 problems run on the MFMA kernel: bf16 operands, fp32 accumulation and softmax state,
+ * probabilities rounded to bf16 before the PV product; supported (B, D): (64,64), (64,128),
+ * (128,128) and (128,64).  f32 problems run on a plain fp32 kernel for B <= 128, D in {32,64,128}.
+ * Anything else: CA_ERR_UNSUPPORTED. */
+int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
+                         void* stream);
+
+/* Same kernel with every query tile keeping all n tiles (the full-attention starting point of
+ * Sec. 4.2 and the baseline of Sec. 5.1); the per-head windows of the layout are ignored. */
+int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
+                       void* stream);
+
+/* Message of the last failure on the calling thread ("" if none); valid until the next call. */
+const char* compact_attn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMPACT_ATTN_H */

@@ -1,0 +1,247 @@
+"""ctypes binding of libcompact_attn.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see
+include/compact_attn.h).  Tensors are torch tensors used purely as device
+buffers; their data pointers and the current torch stream are handed to the
+library.  There is no fallback: if the shared library is missing or a call
+fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcompact_attn.so")
+
+CA_OK = 0
+CA_ERR_INVALID_ARG = -1
+CA_ERR_UNSUPPORTED = -2
+CA_ERR_ALLOC = -3
+CA_ERR_HIP = -4
+CA_F32 = 0
+CA_BF16 = 1
+CA_MAX_GROUPS = 8
+
+EXPORTED = (
+    "compact_attn_build_layout",
+    "compact_attn_layout_info",
+    "compact_attn_layout_csr",
+    "compact_attn_layout_order",
+    "compact_attn_layout_upload",
+    "compact_attn_free_layout",
+    "compact_attn_permute",
+    "compact_attn_forward",
+    "compact_attn_dense",
+    "compact_attn_last_error",
+)
+
+
+class ca_window(ctypes.Structure):
+    _fields_ = [("rh", ctypes.c_int32), ("rw", ctypes.c_int32)]
+
+
+class ca_group(ctypes.Structure):
+    _fields_ = [("max_dt", ctypes.c_int32), ("a", ca_window), ("b", ca_window)]
+
+
+class ca_head(ctypes.Structure):
+    _fields_ = [("num_groups", ctypes.c_int32), ("groups", ctypes.POINTER(ca_group))]
+
+
+class ca_problem(ctypes.Structure):
+    _fields_ = [
+        ("T", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+        ("tt", ctypes.c_int32), ("th", ctypes.c_int32), ("tw", ctypes.c_int32),
+        ("n_text", ctypes.c_int32),
+        ("batch", ctypes.c_int32), ("num_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+    ]
+
+
+class CompactAttnError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"compact_attn status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libcompact_attn.so (built in-tree by paper_2508_12969_amd.build). No fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2508_12969_amd.build` "
+            "(there is no CPU or PyTorch fallback)"
+        )
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
+    lib.compact_attn_build_layout.argtypes = [ctypes.POINTER(ca_problem), ctypes.POINTER(ca_head), ctypes.POINTER(vp)]
+    lib.compact_attn_layout_info.argtypes = [vp, i64p, i64p, i64p, i64p, i64p]
+    lib.compact_attn_layout_csr.argtypes = [vp, i32, ctypes.POINTER(i64p), ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
+    lib.compact_attn_layout_order.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
+    lib.compact_attn_layout_upload.argtypes = [vp]
+    lib.compact_attn_free_layout.argtypes = [vp]
+    lib.compact_attn_free_layout.restype = None
+    lib.compact_attn_permute.argtypes = [vp, vp, vp, i32, vp]
+    lib.compact_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.compact_attn_dense.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.compact_attn_last_error.argtypes = []
+    lib.compact_attn_last_error.restype = ctypes.c_char_p
+    for name in EXPORTED:
+        if name not in ("compact_attn_free_layout", "compact_attn_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def compact_attn_last_error():
+    return load_library().compact_attn_last_error().decode()
+
+
+def _check(status):
+    if status != CA_OK:
+        raise CompactAttnError(status, compact_attn_last_error())
+
+
+class Layout:
+    """Owner of a ca_layout*; keeps the problem description for shape checks."""
+
+    def __init__(self, handle, problem):
+        self.handle = handle
+        self.problem = problem
+        n, B, n_real, n_pad, nnz = (ctypes.c_int64() for _ in range(5))
+        _check(load_library().compact_attn_layout_info(handle, n, B, n_real, n_pad, nnz))
+        self.n_tiles, self.tokens_per_tile = n.value, B.value
+        self.n_tokens_real, self.n_tokens_padded, self.nnz_total = n_real.value, n_pad.value, nnz.value
+
+    def free(self):
+        if self.handle is not None:
+            load_library().compact_attn_free_layout(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    def shape(self, padded):
+        p = self.problem
+        return (p.batch, p.num_heads, self.n_tokens_padded if padded else self.n_tokens_real, p.head_dim)
+
+
+def compact_attn_build_layout(T, H, W, tile, n_text, batch, num_heads, head_dim, dtype, heads, scale=0.0):
+    """heads: per head a list of (max_dt, (rh, rw), (rh, rw)); dtype "f32" or "bf16"."""
+    lib = load_library()
+    if len(heads) != num_heads:
+        raise ValueError("one head description per head is required")
+    prob = ca_problem(T, H, W, tile[0], tile[1], tile[2], n_text, batch, num_heads, head_dim,
+                      {"f32": CA_F32, "bf16": CA_BF16}[dtype], scale)
+    keep = []
+    c_heads = (ca_head * num_heads)()
+    for i, groups in enumerate(heads):
+        arr = (ca_group * max(len(groups), 1))()
+        for j, (max_dt, a, b) in enumerate(groups):
+            arr[j] = ca_group(max_dt, ca_window(*a), ca_window(*b))
+        keep.append(arr)
+        c_heads[i].num_groups = len(groups)
+        c_heads[i].groups = ctypes.cast(arr, ctypes.POINTER(ca_group))
+    handle = ctypes.c_void_p()
+    _check(lib.compact_attn_build_layout(ctypes.byref(prob), c_heads, ctypes.byref(handle)))
+    return Layout(handle, prob)
+
+
+def compact_attn_layout_info(layout):
+    return dict(n_tiles=layout.n_tiles, tokens_per_tile=layout.tokens_per_tile, n_tokens_real=layout.n_tokens_real,
+                n_tokens_padded=layout.n_tokens_padded, nnz_total=layout.nnz_total)
+
+
+def compact_attn_layout_csr(layout, head):
+    """(row_ptr int64[n+1], col_idx int32[nnz_head]) copied out of the layout."""
+    rp = ctypes.POINTER(ctypes.c_int64)()
+    ci = ctypes.POINTER(ctypes.c_int32)()
+    _check(load_library().compact_attn_layout_csr(layout.handle, head, ctypes.byref(rp), ctypes.byref(ci)))
+    row_ptr = np.ctypeslib.as_array(rp, shape=(layout.n_tiles + 1,)).copy()
+    nnz = int(row_ptr[-1])
+    col_idx = np.ctypeslib.as_array(ci, shape=(nnz,)).copy() if nnz else np.zeros(0, np.int32)
+    return row_ptr, col_idx
+
+
+def compact_attn_layout_order(layout):
+    o = ctypes.POINTER(ctypes.c_int32)()
+    _check(load_library().compact_attn_layout_order(layout.handle, ctypes.byref(o)))
+    return np.ctypeslib.as_array(o, shape=(layout.problem.num_heads * layout.n_tiles,)).copy()
+
+
+def compact_attn_layout_upload(layout):
+    _check(load_library().compact_attn_layout_upload(layout.handle))
+
+
+def compact_attn_free_layout(layout):
+    layout.free()
+
+
+def _torch_dtype(layout):
+    import torch
+    return torch.bfloat16 if layout.problem.dtype == CA_BF16 else torch.float32
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_tensor(t, layout, padded, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if t.dtype != _torch_dtype(layout):
+        raise ValueError(f"{name} has dtype {t.dtype}, layout expects {_torch_dtype(layout)}")
+    if tuple(t.shape) != layout.shape(padded):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {layout.shape(padded)}")
+
+
+def compact_attn_permute(src, layout, inverse=False, out=None, stream=None):
+    """natural order -> tile order (inverse=False) or back (inverse=True)."""
+    import torch
+    _check_tensor(src, layout, padded=bool(inverse), name="src")
+    if out is None:
+        out = torch.empty(layout.shape(padded=not inverse), dtype=src.dtype, device=src.device)
+    _check_tensor(out, layout, padded=not inverse, name="out")
+    _check(load_library().compact_attn_permute(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                               layout.handle, int(bool(inverse)), _stream_ptr(stream)))
+    return out
+
+
+def _attention(fn, q, k, v, layout, out, stream):
+    import torch
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        _check_tensor(t, layout, True, name)
+    if out is None:
+        out = torch.empty_like(q)
+    _check_tensor(out, layout, True, "out")
+    _check(fn(ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+              layout.handle, ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)))
+    return out
+
+
+def compact_attn_forward(q, k, v, layout, out=None, stream=None):
+    """Sparse attention over tile-ordered, padded q/k/v [batch, heads, N_pad, D]."""
+    return _attention(load_library().compact_attn_forward, q, k, v, layout, out, stream)
+
+
+def compact_attn_dense(q, k, v, layout, out=None, stream=None):
+    """Same kernel with every query tile keeping all tiles."""
+    return _attention(load_library().compact_attn_dense, q, k, v, layout, out, stream)

@@ -1,0 +1,260 @@
+// C-ABI entry points: argument checking, layout life cycle, device upload, kernel dispatch.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "kernels.h"
+#include "layout.h"
+
+using ca::set_error;
+
+namespace {
+
+int fail(int status, const char* what) {
+  set_error("%s", what);
+  return status;
+}
+
+int hip_fail(hipError_t e, const char* where) {
+  set_error("%s: %s", where, hipGetErrorString(e));
+  return CA_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int elem_size(int32_t dtype) { return dtype == CA_BF16 ? 2 : 4; }
+
+template <class T>
+int upload_vec(const T* host, size_t count, T** dev) {
+  *dev = nullptr;
+  const size_t bytes = (count ? count : 1) * sizeof(T);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(dev), bytes);
+  if (e != hipSuccess) {
+    set_error("hipMalloc of %zu bytes for a layout table failed: %s", bytes, hipGetErrorString(e));
+    (void)hipGetLastError();
+    return CA_ERR_ALLOC;
+  }
+  if (count) {
+    e = hipMemcpy(*dev, host, count * sizeof(T), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy of a layout table");
+  }
+  return CA_OK;
+}
+
+void free_device_tables(ca::DeviceTables& d) {
+  if (d.row_ptr) (void)hipFree(d.row_ptr);
+  if (d.col_idx) (void)hipFree(d.col_idx);
+  if (d.order) (void)hipFree(d.order);
+  if (d.tile_class) (void)hipFree(d.tile_class);
+  if (d.class_mask) (void)hipFree(d.class_mask);
+  d = ca::DeviceTables{};
+}
+
+int ensure_uploaded(ca_layout* L) {
+  std::lock_guard<std::mutex> lock(L->upload_mutex);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (L->uploaded) {
+    if (dev != L->device) {
+      set_error("layout tables live on device %d but the current device is %d", L->device, dev);
+      return CA_ERR_INVALID_ARG;
+    }
+    return CA_OK;
+  }
+  ca::DeviceTables d;
+  int st = upload_vec(L->row_ptr.data(), L->row_ptr.size(), &d.row_ptr);
+  if (st == CA_OK) st = upload_vec(L->col_idx.data(), L->col_idx.size(), &d.col_idx);
+  if (st == CA_OK) st = upload_vec(L->order.data(), L->order.size(), &d.order);
+  if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
+  if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
+  if (st != CA_OK) {
+    free_device_tables(d);
+    return st;
+  }
+  L->dev = d;
+  L->device = dev;
+  L->uploaded = true;
+  return CA_OK;
+}
+
+int check_attn_support(const ca_layout* L) {
+  const ca_problem& p = L->prob;
+  if (p.dtype == CA_BF16) {
+    const bool ok = (L->B == 64 || L->B == 128) && (p.head_dim == 64 || p.head_dim == 128);
+    if (!ok) {
+      set_error("bf16 attention supports tile sizes 64/128 and head_dim 64/128; got B=%lld D=%d", (long long)L->B,
+                p.head_dim);
+      return CA_ERR_UNSUPPORTED;
+    }
+  } else {
+    const bool ok = L->B <= 128 && (p.head_dim == 32 || p.head_dim == 64 || p.head_dim == 128);
+    if (!ok) {
+      set_error("f32 attention supports tile sizes <= 128 and head_dim 32/64/128; got B=%lld D=%d", (long long)L->B,
+                p.head_dim);
+      return CA_ERR_UNSUPPORTED;
+    }
+  }
+  return CA_OK;
+}
+
+int run_attention(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream, bool dense) {
+  ca::clear_error();
+  if (!q || !k || !v || !L || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(CA_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned");
+  if (out == q || out == k || out == v) return fail(CA_ERR_INVALID_ARG, "out must not alias q, k or v");
+  int st = check_attn_support(L);
+  if (st != CA_OK) return st;
+  st = ensure_uploaded(L);
+  if (st != CA_OK) return st;
+  ca::AttnArgs a{};
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.out = out;
+  a.row_ptr = dense ? nullptr : L->dev.row_ptr;
+  a.col_idx = dense ? nullptr : L->dev.col_idx;
+  a.order = dense ? nullptr : L->dev.order;
+  a.tile_class = L->dev.tile_class;
+  a.class_mask = L->dev.class_mask;
+  a.batch = L->prob.batch;
+  a.num_heads = L->prob.num_heads;
+  a.n = L->n;
+  a.B = (int32_t)L->B;
+  a.D = L->prob.head_dim;
+  a.scale = L->scale;
+  const hipError_t e = L->prob.dtype == CA_BF16 ? ca::launch_attn_bf16(a, (hipStream_t)stream)
+                                                : ca::launch_attn_f32(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, dense ? "dense attention launch" : "sparse attention launch");
+  return CA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int compact_attn_build_layout(const ca_problem* problem, const ca_head* heads, ca_layout** out) {
+  ca::clear_error();
+  if (out) *out = nullptr;
+  if (!problem || !heads || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
+  const ca_problem& p = *problem;
+  if (p.T <= 0 || p.H <= 0 || p.W <= 0) return fail(CA_ERR_INVALID_ARG, "T, H, W must be positive");
+  if (p.tt <= 0 || p.th <= 0 || p.tw <= 0) return fail(CA_ERR_INVALID_ARG, "tile dims must be positive");
+  if (p.batch <= 0 || p.num_heads <= 0 || p.head_dim <= 0)
+    return fail(CA_ERR_INVALID_ARG, "batch, num_heads, head_dim must be positive");
+  if (p.dtype != CA_F32 && p.dtype != CA_BF16) return fail(CA_ERR_INVALID_ARG, "unknown dtype");
+  if (!(p.scale == p.scale) || std::isinf(p.scale)) return fail(CA_ERR_INVALID_ARG, "scale is not finite");
+  const int64_t B = (int64_t)p.tt * p.th * p.tw;
+  if (B > (1 << 20)) return fail(CA_ERR_INVALID_ARG, "tile too large");
+  if (p.n_text < 0 || p.n_text % B != 0) return fail(CA_ERR_INVALID_ARG, "n_text must be a non-negative multiple of tt*th*tw");
+  if (((int64_t)p.head_dim * elem_size(p.dtype)) % 16 != 0)
+    return fail(CA_ERR_INVALID_ARG, "head_dim * element size must be a multiple of 16 bytes");
+  const int64_t nT = ceil_div(p.T, p.tt), nH = ceil_div(p.H, p.th), nW = ceil_div(p.W, p.tw);
+  const int64_t n = nT * nH * nW + p.n_text / B;
+  if (n * B >= (int64_t)1 << 31 || (int64_t)p.num_heads * n >= (int64_t)1 << 31)
+    return fail(CA_ERR_INVALID_ARG, "problem too large for 32-bit tile/row ids");
+
+  ca_layout* L = new (std::nothrow) ca_layout();
+  if (!L) return fail(CA_ERR_ALLOC, "out of host memory");
+  L->prob = p;
+  L->nT = (int32_t)nT;
+  L->nH = (int32_t)nH;
+  L->nW = (int32_t)nW;
+  L->B = B;
+  L->n_vid = nT * nH * nW;
+  L->n_txt = p.n_text / B;
+  L->n = n;
+  L->N_real = (int64_t)p.T * p.H * p.W + p.n_text;
+  L->N_pad = n * B;
+  L->scale = p.scale > 0.f ? p.scale : 1.0f / std::sqrt((float)p.head_dim);
+  const int st = ca::build_host_tables(*L, heads);
+  if (st != CA_OK) {
+    delete L;
+    return st;
+  }
+  *out = L;
+  return CA_OK;
+}
+
+int compact_attn_layout_info(const ca_layout* L, int64_t* n_tiles, int64_t* tokens_per_tile, int64_t* n_tokens_real,
+                             int64_t* n_tokens_padded, int64_t* nnz_total) {
+  ca::clear_error();
+  if (!L) return fail(CA_ERR_INVALID_ARG, "null layout");
+  if (n_tiles) *n_tiles = L->n;
+  if (tokens_per_tile) *tokens_per_tile = L->B;
+  if (n_tokens_real) *n_tokens_real = L->N_real;
+  if (n_tokens_padded) *n_tokens_padded = L->N_pad;
+  if (nnz_total) *nnz_total = (int64_t)L->col_idx.size();
+  return CA_OK;
+}
+
+int compact_attn_layout_csr(const ca_layout* L, int32_t head, const int64_t** row_ptr, const int32_t** col_idx) {
+  ca::clear_error();
+  if (!L || !row_ptr || !col_idx) return fail(CA_ERR_INVALID_ARG, "null argument");
+  if (head < 0 || head >= L->prob.num_heads) return fail(CA_ERR_INVALID_ARG, "head out of range");
+  *row_ptr = L->head_row_ptr[head].data();
+  *col_idx = L->col_idx.data() + L->row_ptr[(int64_t)head * L->n];
+  return CA_OK;
+}
+
+int compact_attn_layout_order(const ca_layout* L, const int32_t** order) {
+  ca::clear_error();
+  if (!L || !order) return fail(CA_ERR_INVALID_ARG, "null argument");
+  *order = L->order.data();
+  return CA_OK;
+}
+
+int compact_attn_layout_upload(ca_layout* L) {
+  ca::clear_error();
+  if (!L) return fail(CA_ERR_INVALID_ARG, "null layout");
+  return ensure_uploaded(L);
+}
+
+void compact_attn_free_layout(ca_layout* L) {
+  if (!L) return;
+  if (L->uploaded) free_device_tables(L->dev);
+  delete L;
+}
+
+int compact_attn_permute(const void* src, void* dst, ca_layout* L, int32_t inverse, void* stream) {
+  ca::clear_error();
+  if (!src || !dst || !L) return fail(CA_ERR_INVALID_ARG, "null argument");
+  if (!aligned16(src) || !aligned16(dst)) return fail(CA_ERR_INVALID_ARG, "src and dst must be 16-byte aligned");
+  if (src == dst) return fail(CA_ERR_INVALID_ARG, "src and dst must not overlap");
+  if (inverse != 0 && inverse != 1) return fail(CA_ERR_INVALID_ARG, "inverse must be 0 or 1");
+  const ca_problem& p = L->prob;
+  ca::PermuteArgs a{};
+  a.src = src;
+  a.dst = dst;
+  a.T = p.T; a.H = p.H; a.W = p.W;
+  a.tt = p.tt; a.th = p.th; a.tw = p.tw;
+  a.nH = L->nH; a.nW = L->nW;
+  a.n_vid = L->n_vid;
+  a.B = L->B;
+  a.N_real = L->N_real;
+  a.N_pad = L->N_pad;
+  a.N_video = (int64_t)p.T * p.H * p.W;
+  a.planes = (int64_t)p.batch * p.num_heads;
+  a.row_bytes = p.head_dim * elem_size(p.dtype);
+  a.inverse = inverse;
+  const hipError_t e = ca::launch_permute(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "permute launch");
+  return CA_OK;
+}
+
+int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {
+  return run_attention(q, k, v, L, out, stream, false);
+}
+
+int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {
+  return run_attention(q, k, v, L, out, stream, true);
+}
+
+const char* compact_attn_last_error(void) { return ca::last_error(); }
+
+}  // extern "C"

@@ -1,0 +1,296 @@
+// Block-sparse attention forward on bf16 MFMA for gfx950 (Appendix D of the paper: a block loop
+// with online softmax that visits only the kept key tiles of each query tile).
+//
+// Work decomposition.  One workgroup owns one (batch, head, query tile) row of the layout and
+// walks that row's kept key tiles.  A wave owns 32 query tokens; the workgroup has B/32 waves.
+//
+// Transposed formulation.  Scores are computed as S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so
+// in the accumulator a lane holds ONE query (column lane%32) and 16 of the 32 keys of a block;
+// its partner lane^32 holds the other 16.  Row max and row sum are therefore register-local
+// except for a single exchange with the partner lane, and the running max / sum / rescale factor
+// are one scalar per lane.  The output is accumulated transposed as well, O^T = V^T P^T, whose
+// B operand (P^T: keys along the contraction, queries across lanes) is exactly the bf16-rounded
+// score accumulator, register for register: no shuffle and no LDS round trip between the two
+// matrix products.  The contraction order over keys inside a 32-key block is permuted (a lane
+// group owns keys {0-3, 8-11, 16-19, 24-27} + 4*group), and the V^T operand is fetched with the
+// same permutation.
+//
+// Operand staging.  K and V tiles go from HBM/L2 straight into LDS (global_load_lds, 16 bytes
+// per lane, no VGPR staging).  K rows are read back as 16-byte row fragments (A operand of
+// S^T).  V stays row-major [key][d] in LDS and is read with ds_read_b64_tr_b16, which hands each
+// lane four consecutive keys of one d column, i.e. the A operand of O^T.  Both tiles are stored
+// with an XOR swizzle of the 16-byte chunk index, applied on the global side of the copy (the LDS
+// side of global_load_lds is lane-contiguous), so that both read patterns spread over all banks.
+//
+// Pipeline.  One K buffer and one V buffer per workgroup: K(j+1) is fetched while the softmax and
+// the PV product of tile j run, V(j+1) while the next QK^T runs.  LDS use is 2*B*D*2 bytes (64 KiB
+// at B = D = 128), which leaves room for two workgroups per CU; their phases drift apart, so one
+// workgroup's softmax (VALU) overlaps the other's matrix products.
+#include "kernels.h"
+
+namespace ca {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef __attribute__((ext_vector_type(4))) short shortx4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Tables that no kernel ever writes are read through the constant address space, which lets the
+// compiler keep wave-uniform reads on the scalar unit even after the loop has issued LDS DMA.
+#define CONST_PTR(T, p) ((const __attribute__((address_space(4))) T*)(p))
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kMinusInf = -__builtin_inff();
+constexpr float kRunningMaxInit = -1e30f;  // finite, so that (m_old - m_new) never forms inf - inf
+
+template <int B_, int D_>
+struct Shape {
+  static constexpr int B = B_, D = D_;
+  static constexpr int kWaves = B / 32;           // one wave per 32 queries
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kKeyBlocks = B / 32;       // 32-key blocks of a key tile
+  static constexpr int kQkSteps = D / 16;         // contraction steps of S^T = K Q^T
+  static constexpr int kDBlocks = D / 32;         // 32-wide blocks of the head dim in O^T
+  static constexpr int kRowBytes = D * 2;
+  static constexpr int kChunksPerRow = D / 8;     // 16-byte chunks
+  static constexpr int kTileBytes = B * D * 2;
+  static constexpr int kLoadsPerThread = kTileBytes / (kThreads * 16);
+  static constexpr int kRowsPerLoad = 1024 / kRowBytes;  // rows covered by one wave-wide 16-byte load
+  static_assert(kLoadsPerThread * kThreads * 16 == kTileBytes, "tile must split evenly");
+};
+
+// Chunk swizzles: logical 16-byte chunk `c` of row `row` lives at physical chunk c ^ f(row).
+// K is read by 16 consecutive rows at one logical chunk: f must take 16 (D=128) or 8x2 (D=64)
+// distinct values.  V is read four rows at a time, 64 contiguous bytes per row: f moves each of
+// the four rows to a different 64-byte group.
+template <int D>
+__device__ __forceinline__ int k_swizzle(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D>
+__device__ __forceinline__ int v_swizzle(int row) {
+  return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+}
+
+template <class S, bool kIsV>
+__device__ __forceinline__ void issue_tile_load(const char* __restrict__ gtile, char* lds_tile, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < S::kLoadsPerThread; ++i) {
+    const int blk = wave * S::kLoadsPerThread + i;  // which KiB of the tile this wave-wide load fills
+    const int row = blk * S::kRowsPerLoad + lane / S::kChunksPerRow;
+    const int phys = lane % S::kChunksPerRow;
+    const int logical = phys ^ (kIsV ? v_swizzle<S::D>(row) : k_swizzle<S::D>(row));
+    const char* g = gtile + row * S::kRowBytes + logical * 16;
+    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(g), LDS_PTR(lds_tile + blk * 1024), 16, 0, 0);
+  }
+}
+
+#define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+#define WAIT_LGKMCNT0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
+#define BARRIER() asm volatile("s_barrier" ::: "memory")
+
+template <int B, int D>
+__global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
+void attn_bf16_kernel(AttnArgs a) {
+  using S = Shape<B, D>;
+  __shared__ __attribute__((aligned(1024))) char lds_k[S::kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_v[S::kTileBytes];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qi = lane & 31;  // query column owned by this lane inside the wave's 32 queries
+  const int g = lane >> 5;   // lane group: which half of every 8-key / 8-d pair this lane holds
+
+  const int64_t rows = (int64_t)a.num_heads * a.n;
+  const int64_t item = blockIdx.x % rows;
+  const int64_t batch = blockIdx.x / rows;
+  const int64_t row = a.order ? a.order[item] : item;
+  const int64_t head = row / a.n, q_tile = row - head * a.n;
+  const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
+  const char* Kp = static_cast<const char*>(a.k) + plane;
+  const char* Vp = static_cast<const char*>(a.v) + plane;
+
+  const int64_t begin = a.row_ptr ? a.row_ptr[row] : 0;
+  const int count = (int)(a.row_ptr ? a.row_ptr[row + 1] - begin : a.n);
+  const auto cols = CONST_PTR(int32_t, a.col_idx ? a.col_idx + begin : nullptr);
+  const auto tile_class = CONST_PTR(int32_t, a.tile_class);
+  const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
+
+  // Q fragment: B operand of S^T, lane (qi, g) holds d = 16*step + 8*g .. +7 of its query.
+  const int64_t q_row = q_tile * B + wave * 32 + qi;
+  bf16x8 qf[S::kQkSteps];
+  {
+    const char* Qp = static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes + g * 16;
+#pragma unroll
+    for (int s = 0; s < S::kQkSteps; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qp + s * 32);
+  }
+
+  floatx16 acc_o[S::kDBlocks];
+#pragma unroll
+  for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
+  float m_run = kRunningMaxInit;  // running max of raw scores of this lane's query
+  float l_run = 0.f;              // this lane's share of the running sum (partner lane holds the rest)
+  const float c2 = a.scale * kLog2e;
+
+  // Per-lane LDS read offsets.
+  // K: row (32*kb + qi), logical chunk 2*step + g.
+  const int k_lane_row_off = qi * S::kRowBytes;
+  const int k_lane_swz = k_swizzle<D>(qi);  // 32*kb does not change the swizzle
+  // V: transposing read; lane covers key row 4*g + (lane%16)/4 (+ 32*kb + 16*t + 8*half) and the
+  // 8-byte half-chunk that holds d = 32*db + 16*((lane/16)%2) + 4*(lane%4) .. +3.
+  const int v_lane_row = 4 * g + ((lane & 15) >> 2);
+  const int v_lane_swz = v_swizzle<D>(v_lane_row);  // multiples of 8 rows keep it (D=128); see below for D=64
+  const int v_lane_chunk = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+  const int v_lane_half = (lane & 1) * 8;
+
+  int kv_tile = 0;
+  if (count > 0) {
+    kv_tile = cols ? cols[0] : 0;
+    issue_tile_load<S, false>(Kp + (int64_t)kv_tile * S::kTileBytes, lds_k, wave, lane);
+    issue_tile_load<S, true>(Vp + (int64_t)kv_tile * S::kTileBytes, lds_v, wave, lane);
+  }
+
+  for (int j = 0; j < count; ++j) {
+    const int next_tile = (j + 1 < count) ? (cols ? cols[j + 1] : j + 1) : 0;
+    const int cls = tile_class[kv_tile];
+
+    // ---- S^T = K Q^T ----------------------------------------------------------------------
+    WAIT_VMCNT(S::kLoadsPerThread);  // K(j) landed (V(j) may still be in flight)
+    BARRIER();
+    floatx16 acc_s[S::kKeyBlocks];
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_s[kb][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < S::kQkSteps; ++s) {
+#pragma unroll
+      for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
+        const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(lds_k + off);
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
+      }
+    }
+    WAIT_LGKMCNT0();
+    BARRIER();  // every wave has finished reading K(j)
+    if (j + 1 < count) issue_tile_load<S, false>(Kp + (int64_t)next_tile * S::kTileBytes, lds_k, wave, lane);
+
+    // ---- padding keys never take part ---------------------------------------------------------
+    if (cls != 0) {
+#pragma unroll
+      for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
+        const uint32_t bits = class_mask[cls * 4 + kb] >> (4 * g);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int bit = 8 * (r / 4) + (r % 4);  // key 32*kb + 8*(r/4) + 4*g + r%4
+          if (!((bits >> bit) & 1u)) acc_s[kb][r] = kMinusInf;
+        }
+      }
+    }
+
+    // ---- online softmax (one query per lane) ---------------------------------------------------
+    float mx = acc_s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    const float mc = m_new * c2;
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[kb][r], c2, -mc));
+        acc_s[kb][r] = p;
+        psum += p;
+      }
+    l_run = l_run * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T ------------------------------------------------------------------------
+    if (j + 1 < count) WAIT_VMCNT(S::kLoadsPerThread);  // V(j) landed (K(j+1) may be in flight)
+    else WAIT_VMCNT(0);
+    BARRIER();
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)acc_s[kb][8 * t + e];
+#pragma unroll
+        for (int db = 0; db < S::kDBlocks; ++db) {
+          const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
+          const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
+          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base));
+          const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base + 8 * S::kRowBytes));
+          bf16x8 vf;
+          vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, acc_o[db], 0, 0, 0);
+        }
+      }
+    }
+    WAIT_LGKMCNT0();
+    BARRIER();  // every wave has finished reading V(j)
+    if (j + 1 < count) issue_tile_load<S, true>(Vp + (int64_t)next_tile * S::kTileBytes, lds_v, wave, lane);
+    kv_tile = next_tile;
+  }
+
+  // ---- epilogue: O = O^T / l, padding queries and empty rows give zeros ------------------------
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const uint32_t q_valid = class_mask[tile_class[q_tile] * 4 + wave];  // slots 32*wave .. +31 are this wave's queries
+  const bool q_real = (q_valid >> qi) & 1u;
+  const float inv = (q_real && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
+  char* Op = static_cast<char*>(a.out) + plane + q_row * S::kRowBytes;
+#pragma unroll
+  for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      bf16x4 o4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc_o[db][4 * r4 + e] * inv);
+      const int d0 = db * 32 + 8 * r4 + 4 * g;
+      *reinterpret_cast<bf16x4*>(Op + d0 * 2) = o4;
+    }
+}
+
+template <int B, int D>
+hipError_t launch(const AttnArgs& a, hipStream_t stream) {
+  const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
+  hipLaunchKernelGGL((attn_bf16_kernel<B, D>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
+  const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
+  if (items == 0) return hipSuccess;
+  if (items > 0x7fffffff) return hipErrorInvalidValue;
+  if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
+  if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
+  if (a.B == 64 && a.D == 128) return launch<64, 128>(a, stream);
+  if (a.B == 64 && a.D == 64) return launch<64, 64>(a, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ca

@@ -1,0 +1,44 @@
+// Launch interfaces of the device kernels.  Each launcher validates nothing: api.cpp has
+// already checked shapes, alignment and support before it calls them.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "layout.h"
+
+namespace ca {
+
+struct PermuteArgs {
+  const void* src;
+  void* dst;
+  int32_t T, H, W, tt, th, tw, nH, nW;
+  int64_t n_vid, B, N_real, N_pad, N_video;
+  int64_t planes;     // batch * num_heads
+  int32_t row_bytes;  // head_dim * sizeof(element), a multiple of 16
+  int32_t inverse;
+};
+hipError_t launch_permute(const PermuteArgs& a, hipStream_t stream);
+
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  void* out;
+  const int64_t* row_ptr;      // device; null selects the dense walk (every row keeps tiles 0..n-1)
+  const int32_t* col_idx;      // device
+  const int32_t* order;        // device; null = identity
+  const int32_t* tile_class;   // device [n]
+  const SlotMask* class_mask;  // device
+  int32_t batch, num_heads;
+  int64_t n;                   // tiles
+  int32_t B, D;
+  float scale;
+};
+// fp32 problems, B <= 128, D in {32, 64, 128}
+hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
+// bf16 problems, (B, D) in {64,128} x {64,128}
+hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace ca

@@ -1,0 +1,215 @@
+// Host-side layout builder: per-head CSR of kept key tiles, launch order and padding masks.
+//
+// Keep rule (Sec. 4.1 of the paper, with Eq. 1 / Eq. 2 read in tile units): the tile-frame
+// distance |kt-qt| selects a group; inside the group a key tile is kept when it lies in either
+// of two query-centred windows, clipped by the tile grid.  Both windows contain the query's own
+// column, so on one tile row of one frame the kept columns form a single interval; the builder
+// walks frames and tile rows in ascending order and emits those intervals, which yields the
+// ascending tile ids directly.  No HIP call is made here.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "layout.h"
+
+namespace ca {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+}
+void clear_error() { g_error[0] = '\0'; }
+const char* last_error() { return g_error; }
+
+namespace {
+
+struct Interval {
+  int32_t lo, hi;  // inclusive; empty when lo > hi
+};
+
+inline Interval clip(int32_t center, int32_t radius, int32_t len) {
+  // radius can be as large as INT32_MAX; widen before adding
+  int64_t lo = (int64_t)center - radius, hi = (int64_t)center + radius;
+  return {(int32_t)std::max<int64_t>(lo, 0), (int32_t)std::min<int64_t>(hi, len - 1)};
+}
+
+inline bool present(const ca_window& w) { return w.rh >= 0 && w.rw >= 0; }
+
+// Resolved windows of one head for every tile-frame distance 0..nT-1 (group lookup done once).
+struct HeadPlan {
+  std::vector<int8_t> has;      // [nT] distance covered by some group
+  std::vector<ca_window> a, b;  // [nT]
+};
+
+int plan_head(const ca_head& h, int32_t head_index, int32_t nT, HeadPlan& plan) {
+  if (h.num_groups < 0 || h.num_groups > CA_MAX_GROUPS) {
+    set_error("head %d: num_groups=%d outside 0..%d", head_index, h.num_groups, CA_MAX_GROUPS);
+    return CA_ERR_INVALID_ARG;
+  }
+  if (h.num_groups > 0 && h.groups == nullptr) {
+    set_error("head %d: groups is null", head_index);
+    return CA_ERR_INVALID_ARG;
+  }
+  int32_t last = -1;
+  for (int32_t g = 0; g < h.num_groups; ++g) {
+    if (h.groups[g].max_dt <= last) {
+      set_error("head %d: max_dt must be non-negative and strictly increasing (group %d has %d after %d)",
+                head_index, g, h.groups[g].max_dt, last);
+      return CA_ERR_INVALID_ARG;
+    }
+    last = h.groups[g].max_dt;
+  }
+  plan.has.assign(nT, 0);
+  plan.a.assign(nT, ca_window{-1, -1});
+  plan.b.assign(nT, ca_window{-1, -1});
+  int32_t g = 0;
+  for (int32_t dt = 0; dt < nT; ++dt) {
+    while (g < h.num_groups && h.groups[g].max_dt < dt) ++g;
+    if (g == h.num_groups) break;
+    plan.has[dt] = 1;
+    plan.a[dt] = h.groups[g].a;
+    plan.b[dt] = h.groups[g].b;
+  }
+  return CA_OK;
+}
+
+// Visits the kept video tiles of query tile (qt,qh,qw) as runs [first_id, first_id+len) in ascending order.
+template <class F>
+inline void for_each_run(const ca_layout& L, const HeadPlan& plan, int32_t qt, int32_t qh, int32_t qw, F&& emit) {
+  for (int32_t kt = 0; kt < L.nT; ++kt) {
+    const int32_t dt = kt > qt ? kt - qt : qt - kt;
+    if (!plan.has[dt]) continue;
+    const ca_window &wa = plan.a[dt], &wb = plan.b[dt];
+    const bool pa = present(wa), pb = present(wb);
+    if (!pa && !pb) continue;
+    Interval ha{0, -1}, hb{0, -1}, ca_{0, -1}, cb{0, -1};
+    if (pa) { ha = clip(qh, wa.rh, L.nH); ca_ = clip(qw, wa.rw, L.nW); }
+    if (pb) { hb = clip(qh, wb.rh, L.nH); cb = clip(qw, wb.rw, L.nW); }
+    const int32_t h_lo = pa && pb ? std::min(ha.lo, hb.lo) : (pa ? ha.lo : hb.lo);
+    const int32_t h_hi = pa && pb ? std::max(ha.hi, hb.hi) : (pa ? ha.hi : hb.hi);
+    for (int32_t kh = h_lo; kh <= h_hi; ++kh) {
+      const bool in_a = pa && kh >= ha.lo && kh <= ha.hi;
+      const bool in_b = pb && kh >= hb.lo && kh <= hb.hi;
+      int32_t lo, hi;
+      if (in_a && in_b) { lo = std::min(ca_.lo, cb.lo); hi = std::max(ca_.hi, cb.hi); }
+      else if (in_a) { lo = ca_.lo; hi = ca_.hi; }
+      else if (in_b) { lo = cb.lo; hi = cb.hi; }
+      else continue;  // rows between two disjoint height ranges cannot occur (both contain qh), kept for safety
+      const int64_t first = ((int64_t)kt * L.nH + kh) * L.nW + lo;
+      emit((int32_t)first, hi - lo + 1);
+    }
+  }
+}
+
+void build_slot_masks(ca_layout& L) {
+  // A tile's padding pattern depends only on whether it is the last tile along each axis.
+  const ca_problem& p = L.prob;
+  const int32_t rem_t = p.T - (L.nT - 1) * p.tt, rem_h = p.H - (L.nH - 1) * p.th, rem_w = p.W - (L.nW - 1) * p.tw;
+  L.class_mask.clear();
+  SlotMask full{};
+  for (int64_t s = 0; s < L.B; ++s) full.w[s >> 5] |= 1u << (s & 31);
+  L.class_mask.push_back(full);
+  int class_of_edge[8];
+  for (int e = 0; e < 8; ++e) {
+    const int32_t lim_t = (e & 4) ? rem_t : p.tt, lim_h = (e & 2) ? rem_h : p.th, lim_w = (e & 1) ? rem_w : p.tw;
+    if (lim_t == p.tt && lim_h == p.th && lim_w == p.tw) { class_of_edge[e] = 0; continue; }
+    SlotMask m{};
+    for (int32_t dt = 0; dt < lim_t; ++dt)
+      for (int32_t dy = 0; dy < lim_h; ++dy)
+        for (int32_t dx = 0; dx < lim_w; ++dx) {
+          const int32_t s = (dt * p.th + dy) * p.tw + dx;
+          m.w[s >> 5] |= 1u << (s & 31);
+        }
+    class_of_edge[e] = (int)L.class_mask.size();
+    L.class_mask.push_back(m);
+  }
+  L.tile_class.assign(L.n, 0);
+  for (int32_t kt = 0; kt < L.nT; ++kt)
+    for (int32_t kh = 0; kh < L.nH; ++kh)
+      for (int32_t kw = 0; kw < L.nW; ++kw) {
+        const int e = (kt == L.nT - 1 ? 4 : 0) | (kh == L.nH - 1 ? 2 : 0) | (kw == L.nW - 1 ? 1 : 0);
+        L.tile_class[((int64_t)kt * L.nH + kh) * L.nW + kw] = class_of_edge[e];
+      }
+}
+
+void build_order(ca_layout& L) {
+  // Descending kept count, ties by ascending row id: a counting sort over counts 0..n.
+  const int64_t rows = (int64_t)L.prob.num_heads * L.n;
+  std::vector<int64_t> bucket_start(L.n + 2, 0);
+  for (int64_t r = 0; r < rows; ++r) {
+    const int64_t c = L.row_ptr[r + 1] - L.row_ptr[r];
+    ++bucket_start[(L.n - c) + 1];  // bucket 0 holds count n, bucket n holds count 0
+  }
+  for (int64_t b = 0; b <= L.n; ++b) bucket_start[b + 1] += bucket_start[b];
+  L.order.resize(rows);
+  for (int64_t r = 0; r < rows; ++r) {
+    const int64_t c = L.row_ptr[r + 1] - L.row_ptr[r];
+    L.order[bucket_start[L.n - c]++] = (int32_t)r;
+  }
+}
+
+}  // namespace
+
+int build_host_tables(ca_layout& L, const ca_head* heads) {
+  const ca_problem& p = L.prob;
+  const int32_t Hd = p.num_heads;
+  std::vector<HeadPlan> plans(Hd);
+  for (int32_t h = 0; h < Hd; ++h) {
+    const int st = plan_head(heads[h], h, L.nT, plans[h]);
+    if (st != CA_OK) return st;
+  }
+  try {
+    const int64_t rows = (int64_t)Hd * L.n;
+    L.row_ptr.assign(rows + 1, 0);
+    // pass 1: row lengths
+    for (int32_t h = 0; h < Hd; ++h)
+      for (int64_t q = 0; q < L.n; ++q) {
+        int64_t cnt;
+        if (q >= L.n_vid) {
+          cnt = L.n;  // text query tile keeps everything
+        } else {
+          const int32_t qw = (int32_t)(q % L.nW), qh = (int32_t)((q / L.nW) % L.nH), qt = (int32_t)(q / ((int64_t)L.nW * L.nH));
+          cnt = L.n_txt;
+          for_each_run(L, plans[h], qt, qh, qw, [&](int32_t, int32_t len) { cnt += len; });
+        }
+        L.row_ptr[(int64_t)h * L.n + q + 1] = cnt;
+      }
+    for (int64_t r = 0; r < rows; ++r) L.row_ptr[r + 1] += L.row_ptr[r];
+    // pass 2: column ids
+    L.col_idx.resize(L.row_ptr[rows]);
+    for (int32_t h = 0; h < Hd; ++h)
+      for (int64_t q = 0; q < L.n; ++q) {
+        int32_t* dst = L.col_idx.data() + L.row_ptr[(int64_t)h * L.n + q];
+        if (q >= L.n_vid) {
+          for (int64_t k = 0; k < L.n; ++k) *dst++ = (int32_t)k;
+          continue;
+        }
+        const int32_t qw = (int32_t)(q % L.nW), qh = (int32_t)((q / L.nW) % L.nH), qt = (int32_t)(q / ((int64_t)L.nW * L.nH));
+        for_each_run(L, plans[h], qt, qh, qw, [&](int32_t first, int32_t len) {
+          for (int32_t i = 0; i < len; ++i) *dst++ = first + i;
+        });
+        for (int64_t k = L.n_vid; k < L.n; ++k) *dst++ = (int32_t)k;
+      }
+    // per-head relative offsets for the C-ABI view
+    L.head_row_ptr.assign(Hd, std::vector<int64_t>());
+    for (int32_t h = 0; h < Hd; ++h) {
+      L.head_row_ptr[h].resize(L.n + 1);
+      const int64_t base = L.row_ptr[(int64_t)h * L.n];
+      for (int64_t q = 0; q <= L.n; ++q) L.head_row_ptr[h][q] = L.row_ptr[(int64_t)h * L.n + q] - base;
+    }
+    build_order(L);
+    build_slot_masks(L);
+  } catch (const std::bad_alloc&) {
+    set_error("out of host memory while building the layout");
+    return CA_ERR_ALLOC;
+  }
+  return CA_OK;
+}
+
+}  // namespace ca

@@ -1,0 +1,59 @@
+// Internal representation of a built layout.  Host tables are filled by layout.cpp (no HIP
+// calls); device copies are created by upload.cpp and consumed by the kernels.
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "compact_attn.h"
+
+namespace ca {
+
+// Validity of the B token slots of a tile, one bit per slot (B <= 128).
+struct SlotMask {
+  uint32_t w[4];
+};
+
+// Device-resident tables.  All pointers are device memory owned by the layout.
+struct DeviceTables {
+  int64_t* row_ptr = nullptr;    // [num_heads*n + 1] offsets into col_idx (global over heads)
+  int32_t* col_idx = nullptr;    // [nnz] kept key tiles, ascending inside each row
+  int32_t* order = nullptr;      // [num_heads*n] launch order of row ids head*n + tile
+  int32_t* tile_class = nullptr; // [n] index into class_mask; 0 = every slot holds a token
+  SlotMask* class_mask = nullptr; // [num_classes]
+};
+
+}  // namespace ca
+
+struct ca_layout {
+  ca_problem prob{};
+  int32_t nT = 0, nH = 0, nW = 0;
+  int64_t B = 0, n_vid = 0, n_txt = 0, n = 0, N_real = 0, N_pad = 0;
+  float scale = 0.f;
+
+  // host tables
+  std::vector<int64_t> row_ptr;             // [num_heads*n + 1], global offsets
+  std::vector<int32_t> col_idx;             // [nnz]
+  std::vector<std::vector<int64_t>> head_row_ptr;  // per head, relative offsets (C-ABI view)
+  std::vector<int32_t> order;               // [num_heads*n]
+  std::vector<int32_t> tile_class;          // [n]
+  std::vector<ca::SlotMask> class_mask;     // class 0 = all valid
+
+  // device tables, created once
+  std::mutex upload_mutex;
+  bool uploaded = false;
+  int device = -1;
+  ca::DeviceTables dev;
+};
+
+namespace ca {
+
+void set_error(const char* fmt, ...);
+void clear_error();
+const char* last_error();
+
+// Fills every host table of `L` from L.prob and the head descriptions.  Returns a ca_status.
+int build_host_tables(ca_layout& L, const ca_head* heads);
+
+}  // namespace ca

@@ -1,0 +1,150 @@
+"""The C-ABI library without a GPU: it loads, exports what the header declares, and its
+host-side layout builder agrees bit for bit with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import paper_2508_12969_amd as ca
+from paper_2508_12969_amd import binding
+from oracle.geometry import Geometry
+from oracle import layout as OL
+from workloads import get_workload, WORKLOAD_NAMES
+
+from helpers import build_layout, geometry_of
+
+ABSENT = (-1, -1)
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    header = open(os.path.join(repo_root, "include", "compact_attn.h")).read()
+    declared = set(re.findall(r"\b(compact_attn_\w+)\s*\(", header))
+    assert declared == set(binding.EXPORTED)
+    lib = ca.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert ca.compact_attn_last_error() == ""
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_small_config_csr_bit_exact(name):
+    wl = get_workload(name)
+    g = geometry_of(wl)
+    lay = build_layout(ca, wl)
+    info = ca.compact_attn_layout_info(lay)
+    assert (info["n_tiles"], info["tokens_per_tile"], info["n_tokens_real"], info["n_tokens_padded"]) == (
+        g.n, g.B, g.N_real, g.N_pad)
+    want = OL.build_csr(g, wl.heads)
+    for h in range(wl.num_heads):
+        row_ptr, col_idx = ca.compact_attn_layout_csr(lay, h)
+        assert row_ptr.dtype == np.int64 and col_idx.dtype == np.int32
+        assert np.array_equal(row_ptr, want[h][0])
+        assert np.array_equal(col_idx, want[h][1])
+    assert info["nnz_total"] == sum(int(w[0][-1]) for w in want)
+    assert np.array_equal(ca.compact_attn_layout_order(lay), OL.work_order(OL.row_counts(g, wl.heads)))
+
+
+@pytest.mark.parametrize("name", [n for n in WORKLOAD_NAMES if n not in ("cfg1", "cfg2")])
+def test_large_config_counts_order_and_sampled_rows(name):
+    wl = get_workload(name)
+    g = geometry_of(wl)
+    lay = build_layout(ca, wl)
+    counts = OL.row_counts(g, wl.heads)                       # closed form, every row
+    rng = np.random.default_rng(11)
+    full_heads = set(int(h) for h in rng.choice(wl.num_heads, 2, replace=False))
+    for h in range(wl.num_heads):
+        row_ptr, col_idx = ca.compact_attn_layout_csr(lay, h)
+        assert np.array_equal(np.diff(row_ptr), counts[h])
+        assert int(row_ptr[-1]) == wl.expected_nnz[h]
+        rows = range(g.n) if h in full_heads else [int(x) for x in rng.choice(g.n, 6, replace=False)] + [0, g.n - 1]
+        if h in full_heads:
+            rows = [int(x) for x in rng.choice(g.n, 60, replace=False)] + [0, g.n_vid - 1, g.n - 1]
+        for q in rows:
+            assert np.array_equal(col_idx[row_ptr[q]:row_ptr[q + 1]], OL.kept_tiles(g, wl.heads[h], q)), (h, q)
+    assert np.array_equal(ca.compact_attn_layout_order(lay), OL.work_order(counts))
+    assert ca.compact_attn_layout_info(lay)["nnz_total"] == int(counts.sum())
+
+
+_win = st.tuples(st.integers(-1, 4), st.integers(-1, 4))
+
+
+@st.composite
+def _cases(draw):
+    tt, th, tw = draw(st.integers(1, 2)), draw(st.integers(1, 3)), draw(st.integers(1, 3))
+    T, H, W = draw(st.integers(1, 5)), draw(st.integers(1, 7)), draw(st.integers(1, 7))
+    n_txt = draw(st.integers(0, 2))
+    heads = []
+    for _ in range(draw(st.integers(1, 3))):
+        k = draw(st.integers(0, 3))
+        dts = sorted(draw(st.sets(st.integers(0, 6), min_size=k, max_size=k)))
+        heads.append([(dt, draw(_win), draw(_win)) for dt in dts])
+    return (T, H, W, (tt, th, tw), n_txt * tt * th * tw, heads)
+
+
+@settings(max_examples=150, deadline=None)
+@given(_cases())
+def test_random_small_layouts_bit_exact(case):
+    T, H, W, tile, n_text, heads = case
+    g = Geometry(T, H, W, *tile, n_text)
+    lay = ca.compact_attn_build_layout(T, H, W, tile, n_text, 1, len(heads), 8, "f32", heads)
+    want = OL.build_csr(g, heads)
+    for h in range(len(heads)):
+        row_ptr, col_idx = ca.compact_attn_layout_csr(lay, h)
+        assert np.array_equal(row_ptr, want[h][0]) and np.array_equal(col_idx, want[h][1])
+    assert np.array_equal(ca.compact_attn_layout_order(lay), OL.work_order(OL.row_counts(g, heads)))
+    lay.free()
+
+
+def test_huge_radius_and_many_groups():
+    heads = [[(i, (2 ** 31 - 1, 0), (0, 2 ** 31 - 1)) for i in range(8)]]
+    g = Geometry(9, 5, 6, 1, 1, 1)
+    lay = ca.compact_attn_build_layout(9, 5, 6, (1, 1, 1), 0, 1, 1, 8, "f32", heads)
+    want = OL.build_csr(g, heads)
+    row_ptr, col_idx = ca.compact_attn_layout_csr(lay, 0)
+    assert np.array_equal(row_ptr, want[0][0]) and np.array_equal(col_idx, want[0][1])
+
+
+def _expect_error(status, **kw):
+    args = dict(T=2, H=4, W=4, tile=(1, 2, 2), n_text=0, batch=1, num_heads=1, head_dim=8, dtype="f32",
+                heads=[[(0, (0, 0), ABSENT)]])
+    args.update(kw)
+    with pytest.raises(ca.CompactAttnError) as e:
+        ca.compact_attn_build_layout(**args)
+    assert e.value.status == status
+    assert ca.compact_attn_last_error() != ""
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    _expect_error(binding.CA_ERR_INVALID_ARG, T=0)
+    _expect_error(binding.CA_ERR_INVALID_ARG, tile=(1, 0, 2))
+    _expect_error(binding.CA_ERR_INVALID_ARG, n_text=3)
+    _expect_error(binding.CA_ERR_INVALID_ARG, head_dim=3)                                   # 12-byte rows
+    _expect_error(binding.CA_ERR_INVALID_ARG, heads=[[(1, (0, 0), ABSENT), (1, (1, 1), ABSENT)]])
+    _expect_error(binding.CA_ERR_INVALID_ARG, heads=[[(-1, (0, 0), ABSENT)]])
+    _expect_error(binding.CA_ERR_INVALID_ARG, heads=[[(i, (0, 0), ABSENT) for i in range(9)]])
+    _expect_error(binding.CA_ERR_INVALID_ARG, scale=float("nan"))
+    lib = ca.load_library()
+    assert lib.compact_attn_build_layout(None, None, None) == binding.CA_ERR_INVALID_ARG
+    assert lib.compact_attn_layout_info(None, None, None, None, None, None) == binding.CA_ERR_INVALID_ARG
+    assert lib.compact_attn_forward(None, None, None, None, None, None) == binding.CA_ERR_INVALID_ARG
+    assert lib.compact_attn_permute(None, None, None, 0, None) == binding.CA_ERR_INVALID_ARG
+    lib.compact_attn_free_layout(None)
+    # a good call clears the message
+    ca.compact_attn_build_layout(2, 4, 4, (1, 2, 2), 0, 1, 1, 8, "f32", [[(0, (0, 0), ABSENT)]])
+    assert ca.compact_attn_last_error() == ""
+
+
+def test_unsupported_shapes_rejected_before_any_device_work():
+    # bf16 tile of 16 tokens: valid layout, no kernel for it
+    lay = ca.compact_attn_build_layout(2, 4, 4, (1, 4, 4), 0, 1, 1, 64, "bf16", [[(0, (0, 0), ABSENT)]])
+    buf = (ctypes.c_char * 64)()
+    addr = (ctypes.addressof(buf) + 15) & ~15
+    lib = ca.load_library()
+    st_ = lib.compact_attn_forward(addr, addr + 16, addr + 32, lay.handle, addr + 48 - 16 * 3 + 48, None)
+    assert st_ == binding.CA_ERR_UNSUPPORTED
+    assert "bf16" in ca.compact_attn_last_error()
+    assert lib.compact_attn_forward(addr + 1, addr + 16, addr + 32, lay.handle, addr, None) == binding.CA_ERR_INVALID_ARG
+    assert lib.compact_attn_forward(addr, addr + 16, addr + 32, lay.handle, addr, None) == binding.CA_ERR_INVALID_ARG
