@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--workload", default="cfg4-S65")
     ap.add_argument("--dense-calls", type=int, default=3, help="timed calls of the dense kernel (0 = skip)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle leg (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--sweep", action="store_true", help="also time the forward kernel on the other cfg4 sparsities")
     return ap.parse_args()
 
@@ -175,6 +178,13 @@ def main():
             sweep[name] = {"ms": ms, "tflops": f2 / ms / 1e9, "kept": l2.nnz_total / (w2.num_heads * geom.n ** 2),
                            "speedup_vs_dense": (dense_ms / ms) if dense_ms else None}
             l2.free()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = cpu_baseline(wl, geom, q, k, v, args.cpu_seconds) if args.cpu_seconds > 0 else None
 

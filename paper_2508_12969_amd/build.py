@@ -18,7 +18,7 @@ def hipcc_path():
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose=False, extra_flags=()):
+def build(verbose=False, extra_flags=(), out=None):
     """Compile every source for gfx950 and link the shared library. Always recompiles."""
     cmd = [
         hipcc_path(), "-x", "hip", f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -27,7 +27,7 @@ def build(verbose=False, extra_flags=()):
         "-I", INCLUDE, "-I", CSRC,
         *extra_flags,
         *[os.path.join(CSRC, s) for s in SOURCES],
-        "-o", LIB_PATH,
+        "-o", out or LIB_PATH,
     ]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -38,7 +38,7 @@ def build(verbose=False, extra_flags=()):
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err)
-    return LIB_PATH
+    return out or LIB_PATH
 
 
 if __name__ == "__main__":

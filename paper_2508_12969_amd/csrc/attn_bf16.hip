@@ -78,29 +78,74 @@ __device__ __forceinline__ int v_swizzle(int row) {
   return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
+// Asynchronous copy of one B x D tile from global memory into LDS (global_load_lds_dwordx4: each
+// lane moves 16 bytes, the wave's 64 chunks land contiguously at M0 + offset).  Wave `w` fills the
+// KiB blocks [w*L, (w+1)*L) of the tile, L = kLoadsPerThread.  The swizzle is applied on the global
+// side: the lane that fills physical chunk p of LDS row r fetches logical chunk p ^ f(r).
+// Written as inline assembly on purpose: the compiler then does not track these copies and leaves
+// the waiting to the explicit s_waitcnt vmcnt(n) below, which is what lets a copy stay in flight
+// across the matrix products of the other operand.  The instruction offset moves the global and
+// the LDS address together, so a group of four loads shares one M0 value and one scalar base.
 template <class S, bool kIsV>
-__device__ __forceinline__ void issue_tile_load(const char* __restrict__ gtile, char* lds_tile, int wave, int lane) {
+struct TileLoader {
+  static constexpr int kGroups = (S::kLoadsPerThread + 3) / 4;  // loads are issued four per M0 value
+  static constexpr int kPerGroup = S::kLoadsPerThread / kGroups;
+  static_assert(kPerGroup == 4, "four loads per group");
+  uint32_t voff[4];  // per-lane byte offset inside the wave's slice for loads 0..3 of a group
+
+  __device__ __forceinline__ TileLoader(int wave, int lane) {
 #pragma unroll
-  for (int i = 0; i < S::kLoadsPerThread; ++i) {
-    const int blk = wave * S::kLoadsPerThread + i;  // which KiB of the tile this wave-wide load fills
-    const int row = blk * S::kRowsPerLoad + lane / S::kChunksPerRow;
-    const int phys = lane % S::kChunksPerRow;
-    const int logical = phys ^ (kIsV ? v_swizzle<S::D>(row) : k_swizzle<S::D>(row));
-    const char* g = gtile + row * S::kRowBytes + logical * 16;
-    __builtin_amdgcn_global_load_lds(GLOBAL_PTR(g), LDS_PTR(lds_tile + blk * 1024), 16, 0, 0);
+    for (int i = 0; i < 4; ++i) {
+      // the swizzle depends on the row only through bits that repeat every four KiB blocks
+      const int blk = wave * S::kLoadsPerThread + i;
+      const int row = blk * S::kRowsPerLoad + lane / S::kChunksPerRow;
+      const int phys = lane % S::kChunksPerRow;
+      const int logical = phys ^ (kIsV ? v_swizzle<S::D>(row) : k_swizzle<S::D>(row));
+      voff[i] = (uint32_t)((lane / S::kChunksPerRow) * S::kRowBytes + logical * 16);
+    }
   }
-}
+
+  // gtile: global address of the tile (wave-uniform); lds_tile: LDS byte address of the buffer.
+  __device__ __forceinline__ void issue(const char* gtile, uint32_t lds_tile, int wave) const {
+#pragma unroll
+    for (int grp = 0; grp < kGroups; ++grp) {
+      const uint32_t slice = (uint32_t)(wave * S::kLoadsPerThread + grp * 4) * 1024u;
+      const char* sbase = gtile + slice;
+      const uint32_t m0 = lds_tile + slice;
+      asm volatile(
+          "s_mov_b32 m0, %[m0]\n\t"
+          "s_nop 0\n\t"
+          "global_load_lds_dwordx4 %[v0], %[sb] offset:0\n\t"
+          "global_load_lds_dwordx4 %[v1], %[sb] offset:1024\n\t"
+          "global_load_lds_dwordx4 %[v2], %[sb] offset:2048\n\t"
+          "global_load_lds_dwordx4 %[v3], %[sb] offset:3072\n\t"
+          :
+          : [m0] "s"(m0), [v0] "v"(voff[0]), [v1] "v"(voff[1]), [v2] "v"(voff[2]), [v3] "v"(voff[3]), [sb] "s"(sbase)
+          : "memory");
+    }
+  }
+};
 
 #define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 #define WAIT_LGKMCNT0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
 #define BARRIER() asm volatile("s_barrier" ::: "memory")
 
+#ifndef CA_EXP_WPE
+#define CA_EXP_WPE 2
+#endif
+#ifndef CA_EXP_PRIO
+#define CA_EXP_PRIO 0
+#endif
 template <int B, int D>
-__global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
+__global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(CA_EXP_WPE, CA_EXP_WPE)))
 void attn_bf16_kernel(AttnArgs a) {
   using S = Shape<B, D>;
   __shared__ __attribute__((aligned(1024))) char lds_k[S::kTileBytes];
   __shared__ __attribute__((aligned(1024))) char lds_v[S::kTileBytes];
+#ifdef CA_EXP_LDS_PAD
+  __shared__ char lds_pad[CA_EXP_LDS_PAD];
+  if (a.batch < 0) lds_pad[threadIdx.x] = 1;
+#endif
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -129,6 +174,10 @@ void attn_bf16_kernel(AttnArgs a) {
     const char* Qp = static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes + g * 16;
 #pragma unroll
     for (int s = 0; s < S::kQkSteps; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qp + s * 32);
+    // Touch the fragments so that the compiler waits for these loads here, before the loop: inside
+    // the loop the vector-memory counter must belong to the tile copies alone.
+#pragma unroll
+    for (int s = 0; s < S::kQkSteps; ++s) asm volatile("" : "+v"(qf[s]));
   }
 
   floatx16 acc_o[S::kDBlocks];
@@ -151,11 +200,19 @@ void attn_bf16_kernel(AttnArgs a) {
   const int v_lane_chunk = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
   const int v_lane_half = (lane & 1) * 8;
 
+  const TileLoader<S, false> k_loader(wave, lane);
+  const TileLoader<S, true> v_loader(wave, lane);
+  const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_k;
+  const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_v;
+
+#if CA_EXP_PRIO == 1
+  if (__builtin_amdgcn_s_getreg(6148) & 1) __builtin_amdgcn_s_setprio(3);
+#endif
   int kv_tile = 0;
   if (count > 0) {
     kv_tile = cols ? cols[0] : 0;
-    issue_tile_load<S, false>(Kp + (int64_t)kv_tile * S::kTileBytes, lds_k, wave, lane);
-    issue_tile_load<S, true>(Vp + (int64_t)kv_tile * S::kTileBytes, lds_v, wave, lane);
+    k_loader.issue(Kp + (int64_t)kv_tile * S::kTileBytes, lds_k_addr, wave);
+    v_loader.issue(Vp + (int64_t)kv_tile * S::kTileBytes, lds_v_addr, wave);
   }
 
   for (int j = 0; j < count; ++j) {
@@ -165,6 +222,11 @@ void attn_bf16_kernel(AttnArgs a) {
     // ---- S^T = K Q^T ----------------------------------------------------------------------
     WAIT_VMCNT(S::kLoadsPerThread);  // K(j) landed (V(j) may still be in flight)
     BARRIER();
+#if CA_EXP_PRIO == 2
+    __builtin_amdgcn_s_setprio(3);
+#elif CA_EXP_PRIO == 3
+    __builtin_amdgcn_s_setprio(0);
+#endif
     floatx16 acc_s[S::kKeyBlocks];
 #pragma unroll
     for (int kb = 0; kb < S::kKeyBlocks; ++kb)
@@ -181,8 +243,13 @@ void attn_bf16_kernel(AttnArgs a) {
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading K(j)
-    if (j + 1 < count) issue_tile_load<S, false>(Kp + (int64_t)next_tile * S::kTileBytes, lds_k, wave, lane);
+    if (j + 1 < count) k_loader.issue(Kp + (int64_t)next_tile * S::kTileBytes, lds_k_addr, wave);
 
+#if CA_EXP_PRIO == 2
+    __builtin_amdgcn_s_setprio(0);
+#elif CA_EXP_PRIO == 3
+    __builtin_amdgcn_s_setprio(3);
+#endif
     // ---- padding keys never take part ---------------------------------------------------------
     if (cls != 0) {
 #pragma unroll
@@ -228,6 +295,11 @@ void attn_bf16_kernel(AttnArgs a) {
     if (j + 1 < count) WAIT_VMCNT(S::kLoadsPerThread);  // V(j) landed (K(j+1) may be in flight)
     else WAIT_VMCNT(0);
     BARRIER();
+#if CA_EXP_PRIO == 2
+    __builtin_amdgcn_s_setprio(3);
+#elif CA_EXP_PRIO == 3
+    __builtin_amdgcn_s_setprio(0);
+#endif
 #pragma unroll
     for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
 #pragma unroll
@@ -251,7 +323,7 @@ void attn_bf16_kernel(AttnArgs a) {
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V(j)
-    if (j + 1 < count) issue_tile_load<S, true>(Vp + (int64_t)next_tile * S::kTileBytes, lds_v, wave, lane);
+    if (j + 1 < count) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
     kv_tile = next_tile;
   }
 
