@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "kernels.h"
 #include "layout.h"
@@ -47,7 +48,8 @@ int upload_vec(const T* host, size_t count, T** dev) {
 
 void free_device_tables(ca::DeviceTables& d) {
   if (d.row_ptr) (void)hipFree(d.row_ptr);
-  if (d.col_idx) (void)hipFree(d.col_idx);
+  if (d.col_meta) (void)hipFree(d.col_meta);
+  if (d.dense_meta) (void)hipFree(d.dense_meta);
   if (d.order) (void)hipFree(d.order);
   if (d.tile_class) (void)hipFree(d.tile_class);
   if (d.class_mask) (void)hipFree(d.class_mask);
@@ -66,9 +68,26 @@ int ensure_uploaded(ca_layout* L) {
     }
     return CA_OK;
   }
+  // The kernels read one packed word per kept tile: tile id | padding class << 24.
+  if (L->n >= (int64_t)1 << 24 || L->class_mask.size() > 127) {
+    set_error("layout too large for the device tables (%lld tiles, %zu padding classes)", (long long)L->n,
+              L->class_mask.size());
+    return CA_ERR_UNSUPPORTED;
+  }
+  std::vector<int32_t> col_meta, dense_meta;
+  try {
+    col_meta.resize(L->col_idx.size());
+    for (size_t i = 0; i < col_meta.size(); ++i) col_meta[i] = L->col_idx[i] | (L->tile_class[L->col_idx[i]] << 24);
+    dense_meta.resize(L->n);
+    for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)t | (L->tile_class[t] << 24);
+  } catch (const std::bad_alloc&) {
+    set_error("out of host memory while packing the device tables");
+    return CA_ERR_ALLOC;
+  }
   ca::DeviceTables d;
   int st = upload_vec(L->row_ptr.data(), L->row_ptr.size(), &d.row_ptr);
-  if (st == CA_OK) st = upload_vec(L->col_idx.data(), L->col_idx.size(), &d.col_idx);
+  if (st == CA_OK) st = upload_vec(col_meta.data(), col_meta.size(), &d.col_meta);
+  if (st == CA_OK) st = upload_vec(dense_meta.data(), dense_meta.size(), &d.dense_meta);
   if (st == CA_OK) st = upload_vec(L->order.data(), L->order.size(), &d.order);
   if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
@@ -118,7 +137,7 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   a.v = v;
   a.out = out;
   a.row_ptr = dense ? nullptr : L->dev.row_ptr;
-  a.col_idx = dense ? nullptr : L->dev.col_idx;
+  a.col_meta = dense ? L->dev.dense_meta : L->dev.col_meta;
   a.order = dense ? nullptr : L->dev.order;
   a.tile_class = L->dev.tile_class;
   a.class_mask = L->dev.class_mask;

@@ -26,8 +26,8 @@ struct AttnArgs {
   const void* k;
   const void* v;
   void* out;
-  const int64_t* row_ptr;      // device; null selects the dense walk (every row keeps tiles 0..n-1)
-  const int32_t* col_idx;      // device
+  const int64_t* row_ptr;      // device; null selects the dense walk: every row uses col_meta[0..n)
+  const int32_t* col_meta;     // device; per kept tile: tile id | padding class << 24
   const int32_t* order;        // device; null = identity
   const int32_t* tile_class;   // device [n]
   const SlotMask* class_mask;  // device

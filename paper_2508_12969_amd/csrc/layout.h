@@ -18,7 +18,8 @@ struct SlotMask {
 // Device-resident tables.  All pointers are device memory owned by the layout.
 struct DeviceTables {
   int64_t* row_ptr = nullptr;    // [num_heads*n + 1] offsets into col_idx (global over heads)
-  int32_t* col_idx = nullptr;    // [nnz] kept key tiles, ascending inside each row
+  int32_t* col_meta = nullptr;   // [nnz] kept key tiles, ascending inside each row: tile id | class << 24
+  int32_t* dense_meta = nullptr; // [n] the same packing for the list 0..n-1 (dense walk)
   int32_t* order = nullptr;      // [num_heads*n] launch order of row ids head*n + tile
   int32_t* tile_class = nullptr; // [n] index into class_mask; 0 = every slot holds a token
   SlotMask* class_mask = nullptr; // [num_classes]
