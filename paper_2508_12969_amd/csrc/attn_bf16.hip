@@ -68,10 +68,13 @@ struct Shape {
   static constexpr int kRowBytes = D * 2;
   static constexpr int kChunksPerRow = D / 8;     // 16-byte chunks
   static constexpr int kTileBytes = B * D * 2;
-  static constexpr int kLoadsPerThread = kTileBytes / (kThreads * 16);
+  static constexpr int kUnitRows = 64;                   // keys per pipeline unit
+  static constexpr int kUnits = B / kUnitRows;           // units per tile
+  static constexpr int kUnitBytes = kUnitRows * kRowBytes;
+  static constexpr int kLoadsPerThread = kUnitBytes / (kThreads * 16);  // 16-byte loads per lane per unit
   static constexpr int kRowsPerLoad = 1024 / kRowBytes;  // rows covered by one wave-wide 16-byte load
-  static constexpr int kLdsBytes = 4 * kTileBytes;       // K x2, V x2
-  static_assert(kLoadsPerThread * kThreads * 16 == kTileBytes, "tile must split evenly");
+  static constexpr int kLdsBytes = 4 * kUnitBytes;       // two K slots and two V slots of one unit each
+  static_assert(kLoadsPerThread * kThreads * 16 == kUnitBytes, "unit must split evenly");
 };
 
 // Chunk swizzles: logical 16-byte chunk `c` of row `row` lives at physical chunk c ^ f(row).
@@ -87,20 +90,21 @@ __device__ __forceinline__ int v_swizzle(int row) {
   return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
-// Asynchronous copy of one B x D tile from global memory into LDS (global_load_lds_dwordx4: each
+// Asynchronous copy of one unit (64 rows of a B x D tile) from global memory into LDS (global_load_lds_dwordx4: each
 // lane moves 16 bytes, the wave's 64 chunks land contiguously at M0 + offset).  Wave `w` fills the
-// KiB blocks [w*L, (w+1)*L) of the tile, L = kLoadsPerThread.  The swizzle is applied on the global
+// KiB blocks [w*L, (w+1)*L) of the unit, L = kLoadsPerThread.  The swizzle is applied on the global
 // side: the lane that fills physical chunk p of LDS row r fetches logical chunk p ^ f(r).
 // Written as inline assembly on purpose: the compiler then does not track these copies and leaves
 // the waiting to the explicit s_waitcnt below.  The instruction offset moves the global and the
 // LDS address together, so a group of four loads shares one M0 value and one scalar base.
 template <class S, bool kIsV>
-struct TileLoader {
-  static constexpr int kGroups = (S::kLoadsPerThread + 3) / 4;  // loads are issued four per M0 value
-  static_assert(S::kLoadsPerThread == 4 * kGroups, "four loads per group");
+struct UnitLoader {
+  static constexpr int kPerGroup = S::kLoadsPerThread < 4 ? S::kLoadsPerThread : 4;  // loads per M0 value
+  static constexpr int kGroups = S::kLoadsPerThread / kPerGroup;
+  static_assert(kPerGroup * kGroups == S::kLoadsPerThread && (kPerGroup == 2 || kPerGroup == 4), "2 or 4 loads per group");
   uint32_t voff[4];  // per-lane byte offset inside the wave's slice for loads 0..3 of a group
 
-  __device__ __forceinline__ TileLoader(int wave, int lane) {
+  __device__ __forceinline__ UnitLoader(int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       // the swizzle depends on the row only through bits that repeat every four KiB blocks
@@ -112,23 +116,37 @@ struct TileLoader {
     }
   }
 
-  // gtile: global address of the tile (wave-uniform); lds_tile: LDS byte address of the buffer.
-  __device__ __forceinline__ void issue(const char* gtile, uint32_t lds_tile, int wave) const {
+  // gunit: global address of the unit's first row (wave-uniform); lds_slot: LDS byte address.
+  __device__ __forceinline__ void issue(const char* gunit, uint32_t lds_slot, int wave) const {
+#ifdef CA_EXP_NOLOAD
+    return;
+#endif
 #pragma unroll
     for (int grp = 0; grp < kGroups; ++grp) {
-      const uint32_t slice = (uint32_t)(wave * S::kLoadsPerThread + grp * 4) * 1024u;
-      const char* sbase = gtile + slice;
-      const uint32_t m0 = lds_tile + slice;
-      asm volatile(
-          "s_mov_b32 m0, %[m0]\n\t"
-          "s_nop 0\n\t"
-          "global_load_lds_dwordx4 %[v0], %[sb] offset:0\n\t"
-          "global_load_lds_dwordx4 %[v1], %[sb] offset:1024\n\t"
-          "global_load_lds_dwordx4 %[v2], %[sb] offset:2048\n\t"
-          "global_load_lds_dwordx4 %[v3], %[sb] offset:3072\n\t"
-          :
-          : [m0] "s"(m0), [v0] "v"(voff[0]), [v1] "v"(voff[1]), [v2] "v"(voff[2]), [v3] "v"(voff[3]), [sb] "s"(sbase)
-          : "memory");
+      const uint32_t slice = (uint32_t)(wave * S::kLoadsPerThread + grp * kPerGroup) * 1024u;
+      const char* sbase = gunit + slice;
+      const uint32_t m0 = lds_slot + slice;
+      if constexpr (kPerGroup == 4) {
+        asm volatile(
+            "s_mov_b32 m0, %[m0]\n\t"
+            "s_nop 0\n\t"
+            "global_load_lds_dwordx4 %[v0], %[sb] offset:0\n\t"
+            "global_load_lds_dwordx4 %[v1], %[sb] offset:1024\n\t"
+            "global_load_lds_dwordx4 %[v2], %[sb] offset:2048\n\t"
+            "global_load_lds_dwordx4 %[v3], %[sb] offset:3072\n\t"
+            :
+            : [m0] "s"(m0), [v0] "v"(voff[0]), [v1] "v"(voff[1]), [v2] "v"(voff[2]), [v3] "v"(voff[3]), [sb] "s"(sbase)
+            : "memory");
+      } else {
+        asm volatile(
+            "s_mov_b32 m0, %[m0]\n\t"
+            "s_nop 0\n\t"
+            "global_load_lds_dwordx4 %[v0], %[sb] offset:0\n\t"
+            "global_load_lds_dwordx4 %[v1], %[sb] offset:1024\n\t"
+            :
+            : [m0] "s"(m0), [v0] "v"(voff[0]), [v1] "v"(voff[1]), [sb] "s"(sbase)
+            : "memory");
+      }
     }
   }
 };
@@ -361,6 +379,14 @@ __device__ __forceinline__ float pipeline_step(Wave<S>& w, const floatx16 (&s_cu
   return alpha;
 }
 
+#ifdef CA_PROFILE
+// Development aid: per-workgroup cycle totals of the loop phases (wave 0), read back by a debug hook.
+static __device__ unsigned long long g_profile[8 * 65536];
+#define PROF_NOW() __builtin_readcyclecounter()
+#else
+#define PROF_NOW() 0ull
+#endif
+
 // Per kept tile the kernel reads one packed word, tile id | padding class << 24, prefetched three
 // tiles ahead into scalar registers so that no dependent scalar load sits between two steps.
 constexpr int kMetaClassShift = 24;
@@ -370,16 +396,27 @@ template <int B, int D>
 __global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_kernel(AttnArgs a) {
   using S = Shape<B, D>;
-  constexpr int kUnits = B / 64;                       // units per tile
-  constexpr uint32_t kUnitBytes = 64 * S::kRowBytes;   // LDS bytes of a unit's K (or V) rows
-  extern __shared__ __attribute__((aligned(1024))) char lds[];  // K0 K1 V0 V1
+  constexpr int kUnits = S::kUnits;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];  // K slot 0, K slot 1, V slot 0, V slot 1
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  Remap them so
+  // that the workgroups resident on one XCD at a time are `chunk` consecutive entries of the launch
+  // order (same head, neighbouring query tiles, equal list lengths): they walk nearly the same key
+  // tiles at nearly the same time, so one of them pulls a tile into that L2 and the others hit.
   const int64_t rows = (int64_t)a.num_heads * a.n;
-  const int64_t item = blockIdx.x % rows;
-  const int64_t batch = blockIdx.x / rows;
+  int64_t linear = blockIdx.x;
+  {
+    const int64_t span = 8 * (int64_t)a.xcd_chunk, total = rows * a.batch;
+    if (linear < total / span * span) {
+      const int64_t xcd = linear & 7, seq = linear >> 3;
+      linear = (seq / a.xcd_chunk) * span + xcd * a.xcd_chunk + seq % a.xcd_chunk;
+    }
+  }
+  const int64_t item = linear % rows;
+  const int64_t batch = linear / rows;
   const int64_t row = a.order ? (int64_t)a.order[item] : item;
   const int64_t head = row / a.n, q_tile = row - head * a.n;
   const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
@@ -407,14 +444,12 @@ void attn_bf16_kernel(AttnArgs a) {
     for (int s = 0; s < S::kQkSteps; ++s) asm volatile("" : "+v"(w.qf[s]));
   }
 
-  const TileLoader<S, false> k_loader(wave, lane);
-  const TileLoader<S, true> v_loader(wave, lane);
+  const UnitLoader<S, false> k_loader(wave, lane);
+  const UnitLoader<S, true> v_loader(wave, lane);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
-  // LDS address of the K / V rows of unit u (tile u / kUnits, rows 64 * (u % kUnits) ..)
-  auto k_unit = [&](int u) -> uint32_t {
-    return lds_base + (uint32_t)((u / kUnits) & 1) * S::kTileBytes + (uint32_t)(u % kUnits) * kUnitBytes;
-  };
-  auto v_unit = [&](int u) -> uint32_t { return k_unit(u) + 2u * S::kTileBytes; };
+  // LDS slots: the K rows of unit u sit in K slot u&1, its V rows in V slot u&1.
+  auto k_slot = [&](int u) -> uint32_t { return lds_base + (uint32_t)(u & 1) * S::kUnitBytes; };
+  auto v_slot = [&](int u) -> uint32_t { return lds_base + (uint32_t)(2 + (u & 1)) * S::kUnitBytes; };
 
   // Window of packed words for tiles jj .. jj+3 of the row (0 past the end).
   int jj = 0;
@@ -424,54 +459,71 @@ void attn_bf16_kernel(AttnArgs a) {
     w0 = w1; w1 = w2; w2 = w3;
     w3 = jj + 3 < n ? meta[jj + 3] : 0;
   };
-  auto load_k = [&](int32_t word, int j) {
-    k_loader.issue(Kp + (int64_t)(word & kMetaTileMask) * S::kTileBytes, lds_base + (uint32_t)(j & 1) * S::kTileBytes, wave);
+  // Packed word of the tile that holds unit u, for u / kUnits in jj .. jj+2.
+  auto word_of = [&](int u) -> int32_t {
+    const int d = u / kUnits - jj;
+    return d == 0 ? w0 : (d == 1 ? w1 : w2);
   };
-  auto load_v = [&](int32_t word, int j) {
-    v_loader.issue(Vp + (int64_t)(word & kMetaTileMask) * S::kTileBytes,
-                   lds_base + (uint32_t)(2 + (j & 1)) * S::kTileBytes, wave);
+  auto unit_offset = [&](int u) -> int64_t {
+    // wave-uniform by construction; said explicitly so that the address stays in scalar registers
+#ifdef CA_EXP_SAMETILE
+    const uint32_t tile = (uint32_t)__builtin_amdgcn_readfirstlane(word_of(u) & 3);
+#else
+    const uint32_t tile = (uint32_t)__builtin_amdgcn_readfirstlane(word_of(u) & kMetaTileMask);
+#endif
+    const uint32_t half = (uint32_t)__builtin_amdgcn_readfirstlane(u % kUnits);
+    static_assert((S::kTileBytes & (S::kTileBytes - 1)) == 0, "tile size is a power of two");
+    return (int64_t)(((uint64_t)tile << __builtin_ctz(S::kTileBytes)) + half * (uint32_t)S::kUnitBytes);
   };
-  auto mask_if_padded = [&](floatx16 (&s)[2], int32_t word, int half) {
-    const int cls = word >> kMetaClassShift;
+#ifdef CA_EXP_HALFLOAD
+  auto load_k = [&](int u) { if (((u / kUnits) & 1) == 0) k_loader.issue(Kp + unit_offset(u), k_slot(u), wave); };
+  auto load_v = [&](int u) { if (((u / kUnits) & 1) == 0) v_loader.issue(Vp + unit_offset(u), v_slot(u), wave); };
+#else
+  auto load_k = [&](int u) { k_loader.issue(Kp + unit_offset(u), k_slot(u), wave); };
+  auto load_v = [&](int u) { v_loader.issue(Vp + unit_offset(u), v_slot(u), wave); };
+#endif
+  auto mask_if_padded = [&](floatx16 (&s)[2], int u) {
+    const int cls = word_of(u) >> kMetaClassShift;
     if (cls != 0) {
-      const int idx = cls * 4 + 2 * half;
+      const int idx = cls * 4 + 2 * (u % kUnits);
       w.mask_padding(s, class_mask[idx], class_mask[idx + 1]);
     }
   };
-  // Bookkeeping before step u.  Once per tile there is a synchronisation point: every copy issued
-  // at the previous point has landed for every wave, and every wave is done with the buffers that
-  // the next copies overwrite.
-  //   two units per tile: the point is before odd steps u = 2j+1; K(j) and V(j-1) are dead by then
-  //                       -> fetch K(j+2) and V(j+1)
-  //   one unit per tile:  the point is before every step u = j; K(j) and V(j-2) are dead
-  //                       -> fetch K(j+2) and V(j)
-  auto before_step = [&](int u) {
-    if (u > 0 && u % kUnits == 0) advance();   // now jj == u / kUnits
-    if (kUnits == 2 && (u & 1) == 0) return;
-    WAIT_VMCNT0();
-    BARRIER();
-    if (jj + 2 < n) load_k(w2, jj + 2);
-    if (kUnits == 2) {
-      if (jj + 1 < n) load_v(w1, jj + 1);
-    } else {
-      load_v(w0, jj);
-    }
+  const int U = n * kUnits;  // units of this row
+  // Before step u: every copy issued before the previous step has landed for every wave, and every
+  // wave is done with K slot u&1 (unit u, read by the previous step) and V slot u&1 (unit u-2);
+  // then K(u+2) and V(u) are put in flight, to be used by step u+1.
+  unsigned long long prof[6] = {0, 0, 0, 0, 0, 0};
+  unsigned long long prof_t = PROF_NOW();
+  auto prof_mark = [&](int slot) {
+#ifdef CA_PROFILE
+    const unsigned long long now = PROF_NOW();
+    prof[slot] += now - prof_t;
+    prof_t = now;
+#endif
   };
-  // Packed word of the tile that unit u+1 belongs to, while the window sits at tile u / kUnits.
-  auto word_of_next_unit = [&](int u) -> int32_t { return (u + 1) / kUnits == u / kUnits ? w0 : w1; };
+  auto before_step = [&](int u) {
+    prof_mark(4);
+    if (u > 0 && u % kUnits == 0) advance();   // now jj == u / kUnits
+    WAIT_VMCNT0();
+    prof_mark(0);
+    BARRIER();
+    prof_mark(1);
+    if (u + 2 < U) load_k(u + 2);
+    load_v(u);
+    prof_mark(2);
+  };
 
   floatx16 s_a[2], s_b[2];
   bf16x8 p_a[2][2], p_b[2][2];
-  const int U = n * kUnits;  // units of this row
 
   if (n > 0) {
-    load_k(w0, 0);
-    if (n > 1) load_k(w1, 1);
-    if (kUnits == 2) load_v(w0, 0);
+    load_k(0);
+    if (U > 1) load_k(1);
     WAIT_VMCNT0();
     BARRIER();
-    w.qk_all(s_a, k_unit(0));
-    mask_if_padded(s_a, w0, 0);
+    w.qk_all(s_a, k_slot(0));
+    mask_if_padded(s_a, 0);
 
     // step 0 (even state: scores in s_a, probabilities go to p_a)
     before_step(0);
@@ -479,9 +531,9 @@ void attn_bf16_kernel(AttnArgs a) {
       const float alpha = pipeline_step<S, false, false>(w, s_a, s_b, p_b, p_a, 0, 0);
       w.rescale_if_needed(alpha);
     } else {
-      const float alpha = pipeline_step<S, false, true>(w, s_a, s_b, p_b, p_a, k_unit(1), 0);
+      const float alpha = pipeline_step<S, false, true>(w, s_a, s_b, p_b, p_a, k_slot(1), 0);
       w.rescale_if_needed(alpha);
-      mask_if_padded(s_b, word_of_next_unit(0), 1 % kUnits);
+      mask_if_padded(s_b, 1);
       int u = 1;
       for (;;) {
         // odd state: scores in s_b, previous probabilities in p_a
@@ -496,32 +548,41 @@ void attn_bf16_kernel(AttnArgs a) {
         }
         before_step(u);
         {
-          const float alpha1 = pipeline_step<S, true, true>(w, s_b, s_a, p_a, p_b, k_unit(u + 1), v_unit(u - 1));
+          const float alpha1 = pipeline_step<S, true, true>(w, s_b, s_a, p_a, p_b, k_slot(u + 1), v_slot(u - 1));
+          prof_mark(3);
           w.rescale_if_needed(alpha1);
-          mask_if_padded(s_a, word_of_next_unit(u), (u + 1) % kUnits);
+          mask_if_padded(s_a, u + 1);
         }
         ++u;
         // even state: scores in s_a, previous probabilities in p_b
         if (u == U - 1) break;
         before_step(u);
         {
-          const float alpha2 = pipeline_step<S, true, true>(w, s_a, s_b, p_b, p_a, k_unit(u + 1), v_unit(u - 1));
+          const float alpha2 = pipeline_step<S, true, true>(w, s_a, s_b, p_b, p_a, k_slot(u + 1), v_slot(u - 1));
+          prof_mark(3);
           w.rescale_if_needed(alpha2);
-          mask_if_padded(s_b, word_of_next_unit(u), (u + 1) % kUnits);
+          mask_if_padded(s_b, u + 1);
         }
         ++u;
       }
       // last step, even state, u = U-1 >= 1
       before_step(u);
-      const float alpha3 = pipeline_step<S, true, false>(w, s_a, s_b, p_b, p_a, 0, v_unit(u - 1));
+      const float alpha3 = pipeline_step<S, true, false>(w, s_a, s_b, p_b, p_a, 0, v_slot(u - 1));
       w.rescale_if_needed(alpha3);
     }
     // drain: O += V(U-1)^T P(U-1)^T
     WAIT_VMCNT0();
     BARRIER();
-    w.pv_all(p_a, v_unit(U - 1));
+    w.pv_all(p_a, v_slot(U - 1));
   }
 
+#ifdef CA_PROFILE
+  prof_mark(5);
+  if (threadIdx.x == 0 && blockIdx.x < 65536) {
+    for (int i = 0; i < 6; ++i) g_profile[blockIdx.x * 8 + i] = prof[i];
+    g_profile[blockIdx.x * 8 + 6] = (unsigned long long)n;
+  }
+#endif
   // ---- epilogue: O = O^T / l, padding queries and empty rows give zeros ------------------------
   const float l_tot = sum_with_partner(w.l_run);
   // slots 32*wave .. +31 of the query tile are this wave's queries
@@ -553,6 +614,12 @@ hipError_t launch(const AttnArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
+
+#ifdef CA_PROFILE
+extern "C" int compact_attn_debug_read_profile(unsigned long long* host, size_t count) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_profile), count * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
