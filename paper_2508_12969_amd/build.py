@@ -8,11 +8,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libcompact_attn.so")
 SOURCES = ["layout.cpp", "api.cpp", "permute.hip", "attn_f32.hip", "attn_bf16.hip"]
-# The MFMA kernel spells out its instruction interleaving in source order; the machine
-# schedulers would undo it, so they are switched off for that file only.
-PER_FILE_FLAGS = {
-    "attn_bf16.hip": ["-mllvm", "-enable-misched=false", "-mllvm", "-enable-post-misched=false"],
-}
+PER_FILE_FLAGS = {}   # extra hipcc flags for single sources, if any
 ARCH = "gfx950"
 
 

@@ -2,7 +2,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -11,15 +10,6 @@
 #include "layout.h"
 
 using ca::set_error;
-
-namespace ca {
-// development knob
-int xcd_chunk_from_env() {
-  const char* e = getenv("CA_XCD_CHUNK");
-  int v = e ? atoi(e) : 64;
-  return v >= 1 ? v : 1;
-}
-}  // namespace ca
 
 namespace {
 
@@ -157,7 +147,6 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   a.B = (int32_t)L->B;
   a.D = L->prob.head_dim;
   a.scale = L->scale;
-  a.xcd_chunk = ca::xcd_chunk_from_env();
   const hipError_t e = L->prob.dtype == CA_BF16 ? ca::launch_attn_bf16(a, (hipStream_t)stream)
                                                 : ca::launch_attn_f32(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, dense ? "dense attention launch" : "sparse attention launch");

@@ -35,7 +35,6 @@ struct AttnArgs {
   int64_t n;                   // tiles
   int32_t B, D;
   float scale;
-  int32_t xcd_chunk;           // consecutive launch-order entries given to one XCD (>= 1)
 };
 // fp32 problems, B <= 128, D in {32, 64, 128}
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
