@@ -52,6 +52,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMinusInf = -__builtin_inff();
 constexpr float kRunningMaxInit = -1e30f;  // finite, so that (m_old - m_new) never forms inf - inf
 constexpr float kLazyLog2 = 8.0f;          // the exponent reference may lag the row max by 2^8
+constexpr int kXcdChunk = 32;              // consecutive launch-order entries handed to one XCD
 
 template <int B_, int D_>
 struct Shape {
@@ -159,8 +160,20 @@ void attn_bf16_kernel(AttnArgs a) {
   const int g = lane >> 5;   // lane group: which half of every 8-key / 8-d pair this lane holds
 
   const int64_t rows = (int64_t)a.num_heads * a.n;
-  const int64_t item = blockIdx.x % rows;
-  const int64_t batch = blockIdx.x / rows;
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  They are
+  // remapped so that the workgroups resident on one XCD at a time are kXcdChunk consecutive entries
+  // of the launch order (same head, neighbouring query tiles, equal list lengths) instead of every
+  // eighth entry: their key-tile lists overlap, so more of the K/V tile copies hit that L2.
+  int64_t linear = blockIdx.x;
+  {
+    const int64_t span = 8 * (int64_t)kXcdChunk, total = rows * a.batch;
+    if (linear < total / span * span) {
+      const int64_t xcd = linear & 7, seq = linear >> 3;
+      linear = (seq / kXcdChunk) * span + xcd * kXcdChunk + seq % kXcdChunk;
+    }
+  }
+  const int64_t item = linear % rows;
+  const int64_t batch = linear / rows;
   const int64_t row = a.order ? a.order[item] : item;
   const int64_t head = row / a.n, q_tile = row - head * a.n;
   const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
