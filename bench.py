@@ -22,6 +22,12 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
+# HBM bytes of one forward launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of this
+# script scaled by a 1 GiB device copy in the same run (profiles/attn_bf16_kernel_*_pmc.md holds
+# the counters and the command).  A counter run is a separate profiler pass, so the figure is a
+# recorded measurement, not one taken live; workloads without a committed counter run report null.
+MEASURED_TRAFFIC_BYTES = {"cfg4-S65": 105.1e9}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -207,7 +213,9 @@ def main():
         "permute": {"ms_q_k_v": perm3_avg, "gbps": perm_bytes / perm3_avg / 1e6, "pct_hbm_peak": perm_bytes / perm3_avg / 1e6 / 8000 * 100},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": flops / fwd_avg / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "algorithmic_flops_per_launch": flops,
+                     "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * geom.N_pad * D * esz},
         "cpu_baseline": cpu,
     }
     if sweep:
