@@ -40,6 +40,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 typedef __attribute__((ext_vector_type(4))) short shortx4;
 
@@ -50,7 +51,6 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMinusInf = -__builtin_inff();
-constexpr float kRunningMaxInit = -1e30f;  // finite, so that (m_old - m_new) never forms inf - inf
 constexpr float kLazyLog2 = 8.0f;          // the exponent reference may lag the row max by 2^8
 constexpr int kXcdChunk = 32;              // consecutive launch-order entries handed to one XCD
 
@@ -188,6 +188,8 @@ void attn_bf16_kernel(AttnArgs a) {
   const auto tile_class = CONST_PTR(int32_t, a.tile_class);
   const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
 
+  const float c2 = a.scale * kLog2e;
+
   // Q fragment: B operand of S^T, lane (qi, g) holds d = 16*step + 8*g .. +7 of its query.
   const int64_t q_row = q_tile * B + wave * 32 + qi;
   bf16x8 qf[S::kQkSteps];
@@ -206,9 +208,14 @@ void attn_bf16_kernel(AttnArgs a) {
   for (int db = 0; db < S::kDBlocks; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
-  float m_run = kRunningMaxInit;  // exponent reference (a lagging running max) of this lane's query
+  // Exponent reference of this lane's query (raw score units): the first tile's row maximum,
+  // afterwards a lagging running maximum.  neg_m holds -m_run in all 16 registers and is the C operand of the
+  // first contraction step, so the score accumulator comes out as (score - reference).
+  float m_run = 0.f;
+  floatx16 neg_m;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
   float l_run = 0.f;              // this lane's share of the running sum (partner lane holds the rest)
-  const float c2 = a.scale * kLog2e;
 
   // Per-lane LDS read offsets.
   // K: row (32*kb + qi), logical chunk 2*step + g.
@@ -226,13 +233,13 @@ void attn_bf16_kernel(AttnArgs a) {
   const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_k;
   const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_v;
 
+  const float lazy_raw = kLazyLog2 / c2;  // kLazyLog2 in raw score units
   int32_t word = 0;
   if (count > 0) {
     word = meta[0];
     k_loader.issue(Kp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_k_addr, wave);
     v_loader.issue(Vp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_v_addr, wave);
   }
-  const float lazy_raw = kLazyLog2 / c2;  // kLazyLog2 in raw score units
 
   for (int j = 0; j < count; ++j) {
     const int32_t next_word = (j + 1 < count) ? meta[j + 1] : 0;
@@ -244,16 +251,12 @@ void attn_bf16_kernel(AttnArgs a) {
     BARRIER();
     floatx16 acc_s[S::kKeyBlocks];
 #pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc_s[kb][r] = 0.f;
-#pragma unroll
     for (int s = 0; s < S::kQkSteps; ++s) {
 #pragma unroll
       for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
         const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(lds_k + off);
-        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[kb], 0, 0, 0);
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
       }
     }
     WAIT_LGKMCNT0();
@@ -274,33 +277,56 @@ void attn_bf16_kernel(AttnArgs a) {
     }
 
     // ---- online softmax (one query per lane) ---------------------------------------------------
+    // acc_s holds score - reference in raw units.  The reference is set to the row maximum on the
+    // first tile and afterwards moves only for rows whose maximum exceeds it by more than
+    // 2^kLazyLog2; that is a wave-uniform, rarely taken branch, and the common path is exp2 alone.
     float mx = acc_s[0][0];
 #pragma unroll
     for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
     mx = max_with_partner(mx);
-    const float m_new = mx > m_run + lazy_raw ? mx : m_run;   // the reference moves only when it must
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    const float mc = m_new * c2;
-    m_run = m_new;
-    float psum = 0.f;
+    {
+      const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
+      if (j == 0 || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
+        float delta = (j == 0 || mx > lazy_raw) ? mx : 0.f;
+        if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
+        const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
+        m_run += delta;
+        l_run *= alpha;
 #pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[kb][r], c2, -mc));
-        acc_s[kb][r] = p;
-        psum += p;
+          for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
+#pragma unroll
+        for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
       }
-    l_run = l_run * alpha + psum;
-    const uint64_t moved = __builtin_amdgcn_ballot_w64(alpha != 1.0f);
-    // a scalar condition, so that this stays a skipped branch and never runs under a lane mask
-    if (__builtin_amdgcn_readfirstlane((uint32_t)moved | (uint32_t)(moved >> 32)) != 0) {
+    }
+    // probabilities, rounded to bf16 (the B operand of the second product); the row sum adds up the
+    // rounded values, two per v_dot2, so numerator and denominator see the same numbers
+    bf16x8 pf[S::kKeyBlocks][2];
+    {
+      bf16x2 ones;
+      ones[0] = (__bf16)1.0f;
+      ones[1] = (__bf16)1.0f;
 #pragma unroll
-      for (int db = 0; db < S::kDBlocks; ++db)
+      for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
+        for (int t = 0; t < 2; ++t)
+        {
+          bf16x8 p8;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(acc_s[kb][8 * t + e] * c2);
+          pf[kb][t] = p8;
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 0, 1), ones, l_run, false);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 2, 3), ones, l_run, false);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 4, 5), ones, l_run, false);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 6, 7), ones, l_run, false);
+        }
     }
 
     // ---- O^T += V^T P^T ------------------------------------------------------------------------
@@ -311,9 +337,6 @@ void attn_bf16_kernel(AttnArgs a) {
     for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        bf16x8 pf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)acc_s[kb][8 * t + e];
 #pragma unroll
         for (int db = 0; db < S::kDBlocks; ++db) {
           const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
@@ -324,7 +347,7 @@ void attn_bf16_kernel(AttnArgs a) {
               (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base + 8 * S::kRowBytes));
           bf16x8 vf;
           vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, acc_o[db], 0, 0, 0);
+          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], acc_o[db], 0, 0, 0);
         }
       }
     }
