@@ -68,7 +68,8 @@ int ensure_uploaded(ca_layout* L) {
     }
     return CA_OK;
   }
-  // The kernels read one packed word per kept tile: tile id | padding class << 24.
+  // The kernels read one packed word per kept tile: tile id | padding class << 24, and bit 31 set
+  // when the upper half of the tile's slots is padding only (such a tile costs half the products).
   if (L->n >= (int64_t)1 << 24 || L->class_mask.size() > 127) {
     set_error("layout too large for the device tables (%lld tiles, %zu padding classes)", (long long)L->n,
               L->class_mask.size());
@@ -76,10 +77,18 @@ int ensure_uploaded(ca_layout* L) {
   }
   std::vector<int32_t> col_meta, dense_meta;
   try {
+    std::vector<uint32_t> class_word(L->class_mask.size());
+    const int words = (int)((L->B + 31) / 32);
+    for (size_t c = 0; c < class_word.size(); ++c) {
+      bool upper_empty = words >= 2;
+      for (int w = words / 2; w < words; ++w) upper_empty = upper_empty && L->class_mask[c].w[w] == 0;
+      class_word[c] = ((uint32_t)c << 24) | (upper_empty ? 0x80000000u : 0u);
+    }
     col_meta.resize(L->col_idx.size());
-    for (size_t i = 0; i < col_meta.size(); ++i) col_meta[i] = L->col_idx[i] | (L->tile_class[L->col_idx[i]] << 24);
+    for (size_t i = 0; i < col_meta.size(); ++i)
+      col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
     dense_meta.resize(L->n);
-    for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)t | (L->tile_class[t] << 24);
+    for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)((uint32_t)t | class_word[L->tile_class[t]]);
   } catch (const std::bad_alloc&) {
     set_error("out of host memory while packing the device tables");
     return CA_ERR_ALLOC;

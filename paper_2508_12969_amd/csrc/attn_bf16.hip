@@ -80,6 +80,10 @@ void attn_bf16_kernel(AttnArgs a) {
   const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
 
   const float c2 = a.scale * kLog2e;
+  // A wave whose 32 query slots are all padding (the far half of a tile on a padded grid face)
+  // takes part in the tile copies and barriers only.
+  const uint32_t q_valid = class_mask[tile_class[q_tile] * 4 + wave];  // slots 32*wave .. +31 are this wave's queries
+  const bool wave_active = q_valid != 0;
 
   // Q fragment: B operand of S^T, lane (qi, g) holds d = 16*step + 8*g .. +7 of its query.
   const int64_t q_row = q_tile * B + wave * 32 + qi;
@@ -132,121 +136,181 @@ void attn_bf16_kernel(AttnArgs a) {
     v_loader.issue(Vp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_v_addr, wave);
   }
 
-  for (int j = 0; j < count; ++j) {
+  // A wave without real queries only moves tiles: the same copies, waits and barriers as below.
+  const int active_count = wave_active ? count : 0;
+  for (int j = active_count; j < count; ++j) {
+    const int next_tile = (j + 1 < count) ? (meta[j + 1] & 0xffffff) : 0;
+    WAIT_VMCNT(S::kLoadsPerThread);
+    BARRIER();
+    BARRIER();
+    if (j + 1 < count) k_loader.issue(Kp + (int64_t)next_tile * S::kTileBytes, lds_k_addr, wave);
+    if (j + 1 < count) WAIT_VMCNT(S::kLoadsPerThread);
+    else WAIT_VMCNT(0);
+    BARRIER();
+    BARRIER();
+    if (j + 1 < count) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
+  }
+
+  for (int j = 0; j < active_count; ++j) {
     const int32_t next_word = (j + 1 < count) ? meta[j + 1] : 0;
     const int next_tile = next_word & 0xffffff;
-    const int cls = word >> 24;
+    const int cls = (word >> 24) & 0x7f;
+    // keys B/2 .. B-1 of this tile are padding only: the products of the upper key blocks are skipped
+    const bool upper_keys = word >= 0;
 
     // ---- S^T = K Q^T ----------------------------------------------------------------------
     WAIT_VMCNT(S::kLoadsPerThread);  // K(j) landed (V(j) may still be in flight)
     BARRIER();
     floatx16 acc_s[S::kKeyBlocks];
+    constexpr int kLowerBlocks = S::kKeyBlocks / 2;
+    {
 #pragma unroll
-    for (int s = 0; s < S::kQkSteps; ++s) {
+      for (int s = 0; s < S::kQkSteps; ++s) {
 #pragma unroll
-      for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
-        const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(lds_k + off);
-        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
+        for (int kb = 0; kb < kLowerBlocks; ++kb) {
+          const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(lds_k + off);
+          acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
+        }
+      }
+      if (upper_keys) {
+#pragma unroll
+        for (int s = 0; s < S::kQkSteps; ++s) {
+#pragma unroll
+          for (int kb = kLowerBlocks; kb < S::kKeyBlocks; ++kb) {
+            const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(lds_k + off);
+            acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int kb = kLowerBlocks; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_s[kb][r] = kMinusInf;
       }
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading K(j)
     if (j + 1 < count) k_loader.issue(Kp + (int64_t)next_tile * S::kTileBytes, lds_k_addr, wave);
 
-    // ---- padding keys never take part ---------------------------------------------------------
-    // Only tiles on a padded face of the grid have invalid slots (wave-uniform test).  The valid
-    // bits of a 32-key block are one scalar word; the select mask of each score register is built
-    // on the scalar unit (lanes 0-31 hold key 8*(r/4) + r%4 of the block, lanes 32-63 that key + 4)
-    // and applied with one v_cndmask per register.
-    if (cls != 0) {
+    bf16x8 pf[S::kKeyBlocks][2];
+    {
+      // ---- padding keys never take part ---------------------------------------------------------
+      // Only tiles on a padded face of the grid have invalid slots (wave-uniform test).  The valid
+      // bits of a 32-key block are one scalar word; the select mask of each score register is built
+      // on the scalar unit (lanes 0-31 hold key 8*(r/4) + r%4 of the block, lanes 32-63 that key + 4)
+      // and applied with one v_cndmask per register.
+      if (cls != 0) {
 #pragma unroll
-      for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
-        const uint32_t bits = class_mask[cls * 4 + kb];
-        if (bits != 0xffffffffu) {
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
+          const uint32_t bits = class_mask[cls * 4 + kb];
+          if (bits != 0xffffffffu) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int bit = 8 * (r / 4) + (r % 4);
-            const uint32_t lo = 0u - ((bits >> bit) & 1u), hi = 0u - ((bits >> (bit + 4)) & 1u);
-            const uint64_t keep = (uint64_t)lo | ((uint64_t)hi << 32);
-            asm("v_cndmask_b32 %0, %1, %0, %2" : "+v"(acc_s[kb][r]) : "v"(kMinusInf), "s"(keep));
+            for (int r = 0; r < 16; ++r) {
+              const int bit = 8 * (r / 4) + (r % 4);
+              const uint32_t lo = 0u - ((bits >> bit) & 1u), hi = 0u - ((bits >> (bit + 4)) & 1u);
+              const uint64_t keep = (uint64_t)lo | ((uint64_t)hi << 32);
+              asm("v_cndmask_b32 %0, %1, %0, %2" : "+v"(acc_s[kb][r]) : "v"(kMinusInf), "s"(keep));
+            }
           }
         }
       }
-    }
 
-    // ---- online softmax (one query per lane) ---------------------------------------------------
-    // acc_s holds score - reference in raw units.  The reference is set to the row maximum on the
-    // first tile and afterwards moves only for rows whose maximum exceeds it by more than
-    // 2^kLazyLog2; that is a wave-uniform, rarely taken branch, and the common path is exp2 alone.
-    float mx = acc_s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
-    mx = max_with_partner(mx);
-    {
-      const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
-      if (j == 0 || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
-        float delta = (j == 0 || mx > lazy_raw) ? mx : 0.f;
-        if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
-        const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
-        m_run += delta;
-        l_run *= alpha;
-#pragma unroll
-        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
-#pragma unroll
-        for (int db = 0; db < S::kDBlocks; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
-      }
-    }
-    // probabilities, rounded to bf16 (the B operand of the second product); the row sum adds up the
-    // rounded values, two per v_dot2, so numerator and denominator see the same numbers
-    bf16x8 pf[S::kKeyBlocks][2];
-    {
-      bf16x2 ones;
-      ones[0] = (__bf16)1.0f;
-      ones[1] = (__bf16)1.0f;
+      // ---- online softmax (one query per lane) ---------------------------------------------------
+      // acc_s holds score - reference in raw units.  The reference is set to the row maximum on the
+      // first tile and afterwards moves only for rows whose maximum exceeds it by more than
+      // 2^kLazyLog2; that is a wave-uniform, rarely taken branch, and the common path is exp2 alone.
+      float mx = acc_s[0][0];
 #pragma unroll
       for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-        {
-          bf16x8 p8;
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
+      mx = max_with_partner(mx);
+      {
+        const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
+        if (j == 0 || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
+          float delta = (j == 0 || mx > lazy_raw) ? mx : 0.f;
+          if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
+          const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
+          m_run += delta;
+          l_run *= alpha;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(acc_s[kb][8 * t + e] * c2);
-          pf[kb][t] = p8;
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 0, 1), ones, l_run, false);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 2, 3), ones, l_run, false);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 4, 5), ones, l_run, false);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 6, 7), ones, l_run, false);
+          for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
+#pragma unroll
+          for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
         }
+      }
+      // probabilities, rounded to bf16 (the B operand of the second product); the row sum adds up the
+      // rounded values, two per v_dot2, so numerator and denominator see the same numbers
+      {
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
+#pragma unroll
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+          {
+            bf16x8 p8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(acc_s[kb][8 * t + e] * c2);
+            pf[kb][t] = p8;
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 0, 1), ones, l_run, false);
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 2, 3), ones, l_run, false);
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 4, 5), ones, l_run, false);
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 6, 7), ones, l_run, false);
+          }
+      }
     }
 
     // ---- O^T += V^T P^T ------------------------------------------------------------------------
     if (j + 1 < count) WAIT_VMCNT(S::kLoadsPerThread);  // V(j) landed (K(j+1) may be in flight)
     else WAIT_VMCNT(0);
     BARRIER();
+    {
 #pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
+      for (int kb = 0; kb < kLowerBlocks; ++kb) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < 2; ++t) {
 #pragma unroll
-        for (int db = 0; db < S::kDBlocks; ++db) {
-          const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
-          const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
-          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base));
-          const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base + 8 * S::kRowBytes));
-          bf16x8 vf;
-          vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], acc_o[db], 0, 0, 0);
+          for (int db = 0; db < S::kDBlocks; ++db) {
+            const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
+            const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
+            const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base));
+            const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base + 8 * S::kRowBytes));
+            bf16x8 vf;
+            vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], acc_o[db], 0, 0, 0);
+          }
+        }
+      }
+      if (upper_keys) {
+#pragma unroll
+        for (int kb = kLowerBlocks; kb < S::kKeyBlocks; ++kb) {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int db = 0; db < S::kDBlocks; ++db) {
+              const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
+              const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
+              const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                  (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base));
+              const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                  (shortx4 __attribute__((address_space(3)))*)LDS_PTR(lds_v + base + 8 * S::kRowBytes));
+              bf16x8 vf;
+              vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+              acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], acc_o[db], 0, 0, 0);
+            }
+          }
         }
       }
     }
@@ -258,7 +322,6 @@ void attn_bf16_kernel(AttnArgs a) {
 
   // ---- epilogue: O = O^T / l, padding queries and empty rows give zeros ------------------------
   const float l_tot = sum_with_partner(l_run);
-  const uint32_t q_valid = class_mask[tile_class[q_tile] * 4 + wave];  // slots 32*wave .. +31 are this wave's queries
   const bool q_real = (q_valid >> qi) & 1u;
   const float inv = (q_real && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
   char* Op = static_cast<char*>(a.out) + plane + q_row * S::kRowBytes;

@@ -43,9 +43,9 @@ __global__ __launch_bounds__(128) void attn_f32_kernel(AttnArgs a) {
   const int64_t begin = a.row_ptr ? a.row_ptr[row] : 0;
   const int64_t count = a.row_ptr ? a.row_ptr[row + 1] - begin : a.n;
   for (int64_t j = 0; j < count; ++j) {
-    const int32_t word = a.col_meta[begin + j];  // tile id | padding class << 24
+    const int32_t word = a.col_meta[begin + j];  // tile id | padding class << 24 | half-empty flag << 31
     const int64_t kv_tile = word & 0xffffff;
-    const SlotMask kmask = a.class_mask[word >> 24];
+    const SlotMask kmask = a.class_mask[(word >> 24) & 0x7f];
     for (int k0 = 0; k0 < a.B; k0 += kKeysPerStage) {
       const int stage = min(kKeysPerStage, a.B - k0);
       __syncthreads();
