@@ -44,11 +44,42 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, geom, q, k, v, budget_s):
+def executed_fraction(ca, lay, wl):
+    """Share of the nominal matrix products the kernel really issues: a 32-key block or a 32-query
+    wave that holds padding only is skipped, which happens for tiles on a padded face of the grid
+    whose upper half of slots is empty."""
+    import numpy as np
+    tt, th, tw = wl.tile
+    B = tt * th * tw
+    nT, nH, nW = -(-wl.T // tt), -(-wl.H // th), -(-wl.W // tw)
+    n_vid = nT * nH * nW
+    if B < 64:
+        return 1.0
+    a, b, c = np.meshgrid(np.arange(tt), np.arange(th), np.arange(tw), indexing="ij")
+    a, b, c = a.ravel(), b.ravel(), c.ravel()                      # slot -> offsets inside a tile
+    tf, hf, wf = np.unravel_index(np.arange(n_vid), (nT, nH, nW))
+    valid = ((tf[:, None] * tt + a[None] < wl.T) & (hf[:, None] * th + b[None] < wl.H)
+             & (wf[:, None] * tw + c[None] < wl.W))                # [n_vid, B]
+    valid = np.concatenate([valid, np.ones((lay.n_tiles - n_vid, B), bool)])
+    blocks = valid.reshape(lay.n_tiles, B // 32, 32).any(axis=2)    # [n, B/32]
+    q_waves = blocks.sum(axis=1) / (B // 32)                        # active query waves of a tile
+    k_share = np.where(blocks[:, B // 64:].any(axis=1), 1.0, 0.5)   # upper key half skipped when empty
+    done = 0.0
+    for h in range(wl.num_heads):
+        row_ptr, col_idx = ca.compact_attn_layout_csr(lay, h)
+        per_row = np.add.reduceat(k_share[col_idx], row_ptr[:-1]) if len(col_idx) else np.zeros(lay.n_tiles)
+        per_row[np.diff(row_ptr) == 0] = 0.0
+        done += float((per_row * q_waves).sum())
+    return done / lay.nnz_total
+
+
+def cpu_baseline(wl, q, k, v, budget_s):
     """The oracle, as it stands, on a bounded sample of query tiles of the same workload."""
     import numpy as np
     from oracle import attention as OA
     from oracle import layout as OL
+    from oracle.geometry import Geometry
+    geom = Geometry(wl.T, wl.H, wl.W, *wl.tile, wl.n_text)
 
     try:
         from threadpoolctl import threadpool_info
@@ -89,13 +120,11 @@ def main():
     import torch
 
     import paper_2508_12969_amd as ca
-    from oracle.geometry import Geometry
     from workloads import get_workload, make_qkv
 
     torch.cuda.set_device(0)
     dev = "cuda:0"
     wl = get_workload(args.workload)
-    geom = Geometry(wl.T, wl.H, wl.W, *wl.tile, wl.n_text)
 
     def layout_of(w):
         return ca.compact_attn_build_layout(w.T, w.H, w.W, w.tile, w.n_text, w.batch, w.num_heads, w.head_dim, w.dtype, w.heads)
@@ -142,12 +171,13 @@ def main():
     fwd_med = fwd_ms[len(fwd_ms) // 2]
     perm3_avg = sum(perm_ms) / len(perm_ms)
 
-    B, D = geom.B, wl.head_dim
+    B, D, n = lay.tokens_per_tile, wl.head_dim, lay.n_tiles
     flops = lay.nnz_total * wl.batch * 4.0 * B * B * D
-    dense_flops = wl.num_heads * wl.batch * geom.n * geom.n * 4.0 * B * B * D
-    kept = lay.nnz_total / (wl.num_heads * geom.n * geom.n)
+    dense_flops = wl.num_heads * wl.batch * n * n * 4.0 * B * B * D
+    kept = lay.nnz_total / (wl.num_heads * n * n)
+    executed = executed_fraction(ca, lay, wl)
     esz = 2 if wl.dtype == "bf16" else 4
-    perm_bytes = 3 * wl.batch * wl.num_heads * (geom.N_real + geom.N_pad) * D * esz
+    perm_bytes = 3 * wl.batch * wl.num_heads * (lay.n_tokens_real + lay.n_tokens_padded) * D * esz
 
     dense_ms = None
     if args.dense_calls > 0:
@@ -181,7 +211,7 @@ def main():
                 ts.append(a.elapsed_time(b))
             ms = sorted(ts)[len(ts) // 2]
             f2 = l2.nnz_total * 4.0 * B * B * D
-            sweep[name] = {"ms": ms, "tflops": f2 / ms / 1e9, "kept": l2.nnz_total / (w2.num_heads * geom.n ** 2),
+            sweep[name] = {"ms": ms, "tflops": f2 / ms / 1e9, "kept": l2.nnz_total / (w2.num_heads * n ** 2),
                            "speedup_vs_dense": (dense_ms / ms) if dense_ms else None}
             l2.free()
 
@@ -192,7 +222,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    cpu = cpu_baseline(wl, geom, q, k, v, args.cpu_seconds) if args.cpu_seconds > 0 else None
+    cpu = cpu_baseline(wl, q, k, v, args.cpu_seconds) if args.cpu_seconds > 0 else None
 
     rec = {
         "metric": "sparse attention hot path, effective TFLOP/s on kept tiles (permute q,k,v + sparse forward + inverse permute)",
@@ -204,10 +234,11 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={wl.T} H={wl.H} W={wl.W} +{wl.n_text} text, tile {wl.tile}, "
                                f"{wl.num_heads} heads, D={D}, batch {wl.batch}",
-                   "n_tiles": geom.n, "tokens_padded": geom.N_pad, "kept_tile_fraction": kept,
+                   "n_tiles": n, "tokens_padded": lay.n_tokens_padded, "kept_tile_fraction": kept,
                    "layout_build_s": layout_build_s},
         "attn": {"ms_per_call_avg": fwd_avg, "ms_per_call_median": fwd_med, "tflops": flops / fwd_avg / 1e9,
                  "pct_bf16_mfma_peak": 100.0 * flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
+                 "executed_product_fraction": executed, "tflops_executed": executed * flops / fwd_avg / 1e9,
                  "dense_ms": dense_ms, "dense_tflops": (dense_flops / dense_ms / 1e9) if dense_ms else None,
                  "speedup_vs_dense": (dense_ms / fwd_med) if dense_ms else None, "ideal_speedup": 1.0 / kept},
         "permute": {"ms_q_k_v": perm3_avg, "gbps": perm_bytes / perm3_avg / 1e6, "pct_hbm_peak": perm_bytes / perm3_avg / 1e6 / 8000 * 100},
@@ -215,7 +246,7 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "algorithmic_flops_per_launch": flops,
-                     "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * geom.N_pad * D * esz},
+                     "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * lay.n_tokens_padded * D * esz},
         "cpu_baseline": cpu,
     }
     if sweep:

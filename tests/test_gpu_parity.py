@@ -236,6 +236,35 @@ def test_config5_sampled_rows():
     _sampled_parity("cfg5", [4, 6, 13, 17])
 
 
+# ---------------------------------------------------------------- exponent reference moves
+
+@pytest.mark.parametrize("shape", [("bf16", 128, (2, 8, 8)), ("bf16", 128, (1, 8, 8)), ("bf16", 64, (2, 8, 8))])
+def test_rising_and_huge_scores(shape):
+    """Scores that keep rising along the key-tile walk force the kernel to move its exponent
+    reference again and again (rescaling the output tile each time); scores hundreds of units
+    apart must neither overflow nor lose the small terms' normalisation.  The oracle's softmax
+    subtracts the exact row maximum, so it is immune to both."""
+    dtype, D, tile = shape
+    _say("rising scores", shape)
+    T, H, W = 6, 16, 16
+    B = tile[0] * tile[1] * tile[2]
+    heads = [[(T, (1, 1), ABSENT)], [(T, (9, 9), ABSENT)]]
+    wl = make_workload("rising", T, H, W, tile, B, len(heads), D, dtype, heads)
+    g = geometry_of(wl)
+    lay = build_layout(ca, wl)
+    q, k, v = make_qkv(wl, DEV)
+    # keys grow with their position in tile order, so later tiles of every row score higher
+    tok_tile, _ = g.token_tile_and_slot()
+    ramp = torch.tensor(np.asarray(tok_tile), device=DEV, dtype=torch.float32) / g.n
+    for gain, what in ((1.0, "rising"), (40.0, "huge")):
+        kk = (k.float() * (1.0 + 3.0 * gain * ramp[None, None, :, None])).to(k.dtype)
+        qq = (q.float() * (2.0 if gain == 1.0 else 6.0)).to(q.dtype)
+        out, _ = gpu_attention(ca, wl, lay, qq, kk, v)
+        torch.cuda.synchronize()
+        want = OA.masked_attention(g, heads, to_f64(qq[0]), to_f64(kk[0]), to_f64(v[0]), None)
+        _say(what, compare(to_f64(out[0]), want, *tolerances(dtype), what=what))
+
+
 # ---------------------------------------------------------------- determinism
 
 def test_run_to_run_bitwise_identical():
