@@ -94,6 +94,28 @@ typedef struct ca_layout ca_layout; /* opaque; immutable once built; may be shar
  * CA_ERR_ALLOC. */
 int compact_attn_build_layout(const ca_problem* problem, const ca_head* heads, ca_layout** out);
 
+/* Import an arbitrary tile mask (Sec. 3.3: masks are precomputed offline; this is the door for masks
+ * found by any search outside the library).
+ *   row_ptr  host pointer to num_heads host pointers, each int64[n+1] (offsets into that head's col_idx).
+ *   col_idx  host pointer to num_heads host pointers, each int32[row_ptr[h][n]]: kept key-tile ids of
+ *            every query tile, strictly ascending inside a row, in [0, n).
+ * The arrays are copied; nothing is added (no implicit text tiles): the mask is taken as given.
+ * Errors: CA_ERR_INVALID_ARG (null, malformed problem, malformed CSR), CA_ERR_ALLOC. */
+int compact_attn_layout_from_csr(const ca_problem* problem, const int64_t* const* row_ptr,
+                                 const int32_t* const* col_idx, ca_layout** out);
+
+/* Merge two layouts of the same problem by union, row by row (Sec. 4.2: configurations found for
+ * different prompts are merged by union so that every region one of them needs is retained).
+ * *out receives a new layout owned by the caller.  Errors: CA_ERR_INVALID_ARG (null, different
+ * problems), CA_ERR_ALLOC. */
+int compact_attn_layout_union(const ca_layout* a, const ca_layout* b, ca_layout** out);
+
+/* Similarity of two binary tile masks (Eq. 3): |A and B| / |A or B| over the n x n tile pairs of head
+ * head_a of a and head head_b of b; 1 when both are empty.  The layouts must have the same number of
+ * tiles.  Errors: CA_ERR_INVALID_ARG. */
+int compact_attn_layout_similarity(const ca_layout* a, int32_t head_a, const ca_layout* b, int32_t head_b,
+                                   double* sim);
+
 /* Sizes of a layout; any output pointer may be NULL. */
 int compact_attn_layout_info(const ca_layout* layout, int64_t* n_tiles, int64_t* tokens_per_tile,
                              int64_t* n_tokens_real, int64_t* n_tokens_padded, int64_t* nnz_total);

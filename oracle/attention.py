@@ -59,6 +59,29 @@ def attention_tile(geom: Geometry, head, q_tile, q, k, v, scale=None, token_tile
     return (idx, o, J, p) if return_probs else (idx, o)
 
 
+def tile_mask_attention(geom: Geometry, masks, q, k, v, scale=None):
+    """The same definition with the kept set given directly as boolean tile masks.
+
+    masks: bool [num_heads, n, n], masks[h, qt, kt] = query tile qt of head h keeps key tile kt
+    (any block mask, e.g. an imported or merged layout).  q, k, v: [num_heads, N_real, D].
+    """
+    token_tile, _ = geom.token_tile_and_slot()
+    masks = np.asarray(masks, dtype=bool)
+    D = q.shape[-1]
+    if scale is None:
+        scale = default_scale(D)
+    out = np.zeros(q.shape[:-1] + (v.shape[-1],), dtype=np.float64)
+    for h in range(masks.shape[0]):
+        for q_tile in range(geom.n):
+            idx = np.nonzero(token_tile == q_tile)[0]
+            J = np.nonzero(masks[h, q_tile][token_tile])[0]
+            if len(J) == 0 or len(idx) == 0:
+                continue
+            s = scale * (np.asarray(q[h][idx], dtype=np.float64) @ np.asarray(k[h][J], dtype=np.float64).T)
+            out[h, idx] = softmax_rows(s) @ np.asarray(v[h][J], dtype=np.float64)
+    return out
+
+
 def masked_attention(geom: Geometry, heads, q, k, v, scale=None):
     """q, k, v: [num_heads, N_real, D] natural order -> fp64 [num_heads, N_real, D]."""
     token_tile, _ = geom.token_tile_and_slot()

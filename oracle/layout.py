@@ -189,3 +189,28 @@ def mask_similarity(mask_a, mask_b):
     b = np.asarray(mask_b, dtype=bool)
     union = np.logical_or(a, b).sum()
     return 1.0 if union == 0 else float(np.logical_and(a, b).sum()) / float(union)
+
+
+def csr_of_mask(mask):
+    """(row_ptr int64[n+1], col_idx int32[nnz]) of one head's boolean tile mask [n, n], columns ascending."""
+    mask = np.asarray(mask, dtype=bool)
+    counts = mask.sum(axis=1)
+    row_ptr = np.zeros(mask.shape[0] + 1, dtype=np.int64)
+    row_ptr[1:] = np.cumsum(counts)
+    col_idx = np.nonzero(mask)[1].astype(np.int32)
+    return row_ptr, col_idx
+
+
+def mask_of_csr(n, row_ptr, col_idx):
+    """Boolean [n, n] mask of one head's CSR."""
+    mask = np.zeros((n, n), dtype=bool)
+    for q in range(n):
+        mask[q, col_idx[row_ptr[q]:row_ptr[q + 1]]] = True
+    return mask
+
+
+def union_masks(mask_a, mask_b):
+    """Merge of two configurations (Sec. 4.2: configurations found for different prompts are
+    merged by union, so that every region either of them needs is retained)."""
+    return np.logical_or(np.asarray(mask_a, dtype=bool), np.asarray(mask_b, dtype=bool))
+

@@ -12,8 +12,11 @@ from .binding import (  # noqa: F401
     compact_attn_free_layout,
     compact_attn_last_error,
     compact_attn_layout_csr,
+    compact_attn_layout_from_csr,
     compact_attn_layout_info,
     compact_attn_layout_order,
+    compact_attn_layout_similarity,
+    compact_attn_layout_union,
     compact_attn_layout_upload,
     compact_attn_permute,
     library_path,

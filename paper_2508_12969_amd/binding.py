@@ -24,6 +24,9 @@ CA_MAX_GROUPS = 8
 
 EXPORTED = (
     "compact_attn_build_layout",
+    "compact_attn_layout_from_csr",
+    "compact_attn_layout_union",
+    "compact_attn_layout_similarity",
     "compact_attn_layout_info",
     "compact_attn_layout_csr",
     "compact_attn_layout_order",
@@ -85,6 +88,10 @@ def load_library():
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
     lib.compact_attn_build_layout.argtypes = [ctypes.POINTER(ca_problem), ctypes.POINTER(ca_head), ctypes.POINTER(vp)]
+    lib.compact_attn_layout_from_csr.argtypes = [ctypes.POINTER(ca_problem), ctypes.POINTER(i64p),
+                                                 ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)), ctypes.POINTER(vp)]
+    lib.compact_attn_layout_union.argtypes = [vp, vp, ctypes.POINTER(vp)]
+    lib.compact_attn_layout_similarity.argtypes = [vp, i32, vp, i32, ctypes.POINTER(ctypes.c_double)]
     lib.compact_attn_layout_info.argtypes = [vp, i64p, i64p, i64p, i64p, i64p]
     lib.compact_attn_layout_csr.argtypes = [vp, i32, ctypes.POINTER(i64p), ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
     lib.compact_attn_layout_order.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
@@ -158,6 +165,34 @@ def compact_attn_build_layout(T, H, W, tile, n_text, batch, num_heads, head_dim,
     handle = ctypes.c_void_p()
     _check(lib.compact_attn_build_layout(ctypes.byref(prob), c_heads, ctypes.byref(handle)))
     return Layout(handle, prob)
+
+
+def compact_attn_layout_from_csr(T, H, W, tile, n_text, batch, num_heads, head_dim, dtype, csr, scale=0.0):
+    """csr: per head (row_ptr int64[n+1], col_idx int32[nnz]); an arbitrary tile mask, taken as given."""
+    lib = load_library()
+    if len(csr) != num_heads:
+        raise ValueError("one CSR per head is required")
+    prob = ca_problem(T, H, W, tile[0], tile[1], tile[2], n_text, batch, num_heads, head_dim,
+                      {"f32": CA_F32, "bf16": CA_BF16}[dtype], scale)
+    rps = [np.ascontiguousarray(rp, dtype=np.int64) for rp, _ in csr]
+    cis = [np.ascontiguousarray(ci, dtype=np.int32) for _, ci in csr]
+    rp_arr = (ctypes.POINTER(ctypes.c_int64) * num_heads)(*[a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)) for a in rps])
+    ci_arr = (ctypes.POINTER(ctypes.c_int32) * num_heads)(*[a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) for a in cis])
+    handle = ctypes.c_void_p()
+    _check(lib.compact_attn_layout_from_csr(ctypes.byref(prob), rp_arr, ci_arr, ctypes.byref(handle)))
+    return Layout(handle, prob)
+
+
+def compact_attn_layout_union(a, b):
+    handle = ctypes.c_void_p()
+    _check(load_library().compact_attn_layout_union(a.handle, b.handle, ctypes.byref(handle)))
+    return Layout(handle, a.problem)
+
+
+def compact_attn_layout_similarity(a, head_a, b, head_b):
+    sim = ctypes.c_double()
+    _check(load_library().compact_attn_layout_similarity(a.handle, head_a, b.handle, head_b, ctypes.byref(sim)))
+    return sim.value
 
 
 def compact_attn_layout_info(layout):

@@ -162,15 +162,8 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   return CA_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int compact_attn_build_layout(const ca_problem* problem, const ca_head* heads, ca_layout** out) {
-  ca::clear_error();
-  if (out) *out = nullptr;
-  if (!problem || !heads || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
-  const ca_problem& p = *problem;
+// Checks a problem description and allocates a layout with its geometry filled in (no tables yet).
+int new_layout(const ca_problem& p, ca_layout** out) {
   if (p.T <= 0 || p.H <= 0 || p.W <= 0) return fail(CA_ERR_INVALID_ARG, "T, H, W must be positive");
   if (p.tt <= 0 || p.th <= 0 || p.tw <= 0) return fail(CA_ERR_INVALID_ARG, "tile dims must be positive");
   if (p.batch <= 0 || p.num_heads <= 0 || p.head_dim <= 0)
@@ -200,12 +193,76 @@ int compact_attn_build_layout(const ca_problem* problem, const ca_head* heads, c
   L->N_real = (int64_t)p.T * p.H * p.W + p.n_text;
   L->N_pad = n * B;
   L->scale = p.scale > 0.f ? p.scale : 1.0f / std::sqrt((float)p.head_dim);
-  const int st = ca::build_host_tables(*L, heads);
+  *out = L;
+  return CA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int compact_attn_build_layout(const ca_problem* problem, const ca_head* heads, ca_layout** out) {
+  ca::clear_error();
+  if (out) *out = nullptr;
+  if (!problem || !heads || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
+  ca_layout* L = nullptr;
+  int st = new_layout(*problem, &L);
+  if (st != CA_OK) return st;
+  st = ca::build_host_tables(*L, heads);
   if (st != CA_OK) {
     delete L;
     return st;
   }
   *out = L;
+  return CA_OK;
+}
+
+int compact_attn_layout_from_csr(const ca_problem* problem, const int64_t* const* row_ptr, const int32_t* const* col_idx,
+                                 ca_layout** out) {
+  ca::clear_error();
+  if (out) *out = nullptr;
+  if (!problem || !row_ptr || !col_idx || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
+  ca_layout* L = nullptr;
+  int st = new_layout(*problem, &L);
+  if (st != CA_OK) return st;
+  st = ca::import_host_tables(*L, row_ptr, col_idx);
+  if (st != CA_OK) {
+    delete L;
+    return st;
+  }
+  *out = L;
+  return CA_OK;
+}
+
+int compact_attn_layout_union(const ca_layout* a, const ca_layout* b, ca_layout** out) {
+  ca::clear_error();
+  if (out) *out = nullptr;
+  if (!a || !b || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
+  const ca_problem &pa = a->prob, &pb = b->prob;
+  const bool same = pa.T == pb.T && pa.H == pb.H && pa.W == pb.W && pa.tt == pb.tt && pa.th == pb.th && pa.tw == pb.tw &&
+                    pa.n_text == pb.n_text && pa.batch == pb.batch && pa.num_heads == pb.num_heads &&
+                    pa.head_dim == pb.head_dim && pa.dtype == pb.dtype && a->scale == b->scale;
+  if (!same) return fail(CA_ERR_INVALID_ARG, "layouts to merge must describe the same problem");
+  ca_layout* L = nullptr;
+  int st = new_layout(pa, &L);
+  if (st != CA_OK) return st;
+  L->scale = a->scale;
+  st = ca::union_host_tables(*L, *a, *b);
+  if (st != CA_OK) {
+    delete L;
+    return st;
+  }
+  *out = L;
+  return CA_OK;
+}
+
+int compact_attn_layout_similarity(const ca_layout* a, int32_t head_a, const ca_layout* b, int32_t head_b, double* sim) {
+  ca::clear_error();
+  if (!a || !b || !sim) return fail(CA_ERR_INVALID_ARG, "null argument");
+  if (a->n != b->n) return fail(CA_ERR_INVALID_ARG, "layouts must have the same number of tiles");
+  if (head_a < 0 || head_a >= a->prob.num_heads || head_b < 0 || head_b >= b->prob.num_heads)
+    return fail(CA_ERR_INVALID_ARG, "head out of range");
+  *sim = ca::head_similarity(*a, head_a, *b, head_b);
   return CA_OK;
 }
 

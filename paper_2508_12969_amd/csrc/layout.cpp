@@ -156,6 +156,108 @@ void build_order(ca_layout& L) {
 
 }  // namespace
 
+void finish_host_tables(ca_layout& L) {
+  const int32_t Hd = L.prob.num_heads;
+  // per-head relative offsets for the C-ABI view
+  L.head_row_ptr.assign(Hd, std::vector<int64_t>());
+  for (int32_t h = 0; h < Hd; ++h) {
+    L.head_row_ptr[h].resize(L.n + 1);
+    const int64_t base = L.row_ptr[(int64_t)h * L.n];
+    for (int64_t q = 0; q <= L.n; ++q) L.head_row_ptr[h][q] = L.row_ptr[(int64_t)h * L.n + q] - base;
+  }
+  build_order(L);
+  build_slot_masks(L);
+}
+
+int import_host_tables(ca_layout& L, const int64_t* const* row_ptr, const int32_t* const* col_idx) {
+  const int32_t Hd = L.prob.num_heads;
+  for (int32_t h = 0; h < Hd; ++h) {
+    if (!row_ptr[h] || (!col_idx[h] && row_ptr[h][L.n] != 0)) {
+      set_error("head %d: null CSR array", h);
+      return CA_ERR_INVALID_ARG;
+    }
+    if (row_ptr[h][0] != 0) {
+      set_error("head %d: row_ptr[0] must be 0", h);
+      return CA_ERR_INVALID_ARG;
+    }
+    for (int64_t q = 0; q < L.n; ++q) {
+      const int64_t b = row_ptr[h][q], e = row_ptr[h][q + 1];
+      if (e < b || e - b > L.n) {
+        set_error("head %d: row %lld has an invalid extent", h, (long long)q);
+        return CA_ERR_INVALID_ARG;
+      }
+      for (int64_t i = b; i < e; ++i) {
+        const int32_t c = col_idx[h][i];
+        if (c < 0 || c >= L.n || (i > b && c <= col_idx[h][i - 1])) {
+          set_error("head %d: row %lld must list tile ids in [0, n) in strictly ascending order", h, (long long)q);
+          return CA_ERR_INVALID_ARG;
+        }
+      }
+    }
+  }
+  try {
+    const int64_t rows = (int64_t)Hd * L.n;
+    L.row_ptr.assign(rows + 1, 0);
+    int64_t total = 0;
+    for (int32_t h = 0; h < Hd; ++h) {
+      for (int64_t q = 0; q < L.n; ++q) L.row_ptr[(int64_t)h * L.n + q] = total + row_ptr[h][q];
+      total += row_ptr[h][L.n];
+    }
+    L.row_ptr[rows] = total;
+    L.col_idx.resize(total);
+    for (int32_t h = 0; h < Hd; ++h) {
+      const int64_t cnt = row_ptr[h][L.n];
+      if (cnt) std::memcpy(L.col_idx.data() + L.row_ptr[(int64_t)h * L.n], col_idx[h], cnt * sizeof(int32_t));
+    }
+    finish_host_tables(L);
+  } catch (const std::bad_alloc&) {
+    set_error("out of host memory while importing the layout");
+    return CA_ERR_ALLOC;
+  }
+  return CA_OK;
+}
+
+int union_host_tables(ca_layout& L, const ca_layout& a, const ca_layout& b) {
+  try {
+    const int64_t rows = (int64_t)L.prob.num_heads * L.n;
+    L.row_ptr.assign(rows + 1, 0);
+    L.col_idx.clear();
+    L.col_idx.reserve(std::max(a.col_idx.size(), b.col_idx.size()));
+    for (int64_t r = 0; r < rows; ++r) {
+      const int32_t *pa = a.col_idx.data() + a.row_ptr[r], *ea = a.col_idx.data() + a.row_ptr[r + 1];
+      const int32_t *pb = b.col_idx.data() + b.row_ptr[r], *eb = b.col_idx.data() + b.row_ptr[r + 1];
+      while (pa < ea || pb < eb) {  // merge of two ascending lists without duplicates
+        if (pb == eb || (pa < ea && *pa < *pb)) L.col_idx.push_back(*pa++);
+        else if (pa == ea || *pb < *pa) L.col_idx.push_back(*pb++);
+        else { L.col_idx.push_back(*pa++); ++pb; }
+      }
+      L.row_ptr[r + 1] = (int64_t)L.col_idx.size();
+    }
+    finish_host_tables(L);
+  } catch (const std::bad_alloc&) {
+    set_error("out of host memory while merging the layouts");
+    return CA_ERR_ALLOC;
+  }
+  return CA_OK;
+}
+
+double head_similarity(const ca_layout& a, int32_t ha, const ca_layout& b, int32_t hb) {
+  int64_t both = 0, either = 0;
+  for (int64_t q = 0; q < a.n; ++q) {
+    const int64_t ra = (int64_t)ha * a.n + q, rb = (int64_t)hb * b.n + q;
+    const int32_t *pa = a.col_idx.data() + a.row_ptr[ra], *ea = a.col_idx.data() + a.row_ptr[ra + 1];
+    const int32_t *pb = b.col_idx.data() + b.row_ptr[rb], *eb = b.col_idx.data() + b.row_ptr[rb + 1];
+    while (pa < ea && pb < eb) {
+      if (*pa < *pb) ++pa;
+      else if (*pb < *pa) ++pb;
+      else { ++both; ++pa; ++pb; }
+    }
+    either += (a.row_ptr[ra + 1] - a.row_ptr[ra]) + (b.row_ptr[rb + 1] - b.row_ptr[rb]);
+  }
+  either -= both;
+  return either == 0 ? 1.0 : (double)both / (double)either;
+}
+
 int build_host_tables(ca_layout& L, const ca_head* heads) {
   const ca_problem& p = L.prob;
   const int32_t Hd = p.num_heads;
@@ -196,15 +298,7 @@ int build_host_tables(ca_layout& L, const ca_head* heads) {
         });
         for (int64_t k = L.n_vid; k < L.n; ++k) *dst++ = (int32_t)k;
       }
-    // per-head relative offsets for the C-ABI view
-    L.head_row_ptr.assign(Hd, std::vector<int64_t>());
-    for (int32_t h = 0; h < Hd; ++h) {
-      L.head_row_ptr[h].resize(L.n + 1);
-      const int64_t base = L.row_ptr[(int64_t)h * L.n];
-      for (int64_t q = 0; q <= L.n; ++q) L.head_row_ptr[h][q] = L.row_ptr[(int64_t)h * L.n + q] - base;
-    }
-    build_order(L);
-    build_slot_masks(L);
+    finish_host_tables(L);
   } catch (const std::bad_alloc&) {
     set_error("out of host memory while building the layout");
     return CA_ERR_ALLOC;

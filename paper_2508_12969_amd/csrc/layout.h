@@ -56,5 +56,13 @@ const char* last_error();
 
 // Fills every host table of `L` from L.prob and the head descriptions.  Returns a ca_status.
 int build_host_tables(ca_layout& L, const ca_head* heads);
+// The same from per-head CSR arrays (validated: extents, ids in range, strictly ascending rows).
+int import_host_tables(ca_layout& L, const int64_t* const* row_ptr, const int32_t* const* col_idx);
+// Row-wise union of two layouts of the same geometry and head count.
+int union_host_tables(ca_layout& L, const ca_layout& a, const ca_layout& b);
+// |A and B| / |A or B| over the tile pairs of head `ha` of a and head `hb` of b (1 if both are empty).
+double head_similarity(const ca_layout& a, int32_t ha, const ca_layout& b, int32_t hb);
+// Derived tables (per-head views, launch order, padding classes) once row_ptr / col_idx are set.
+void finish_host_tables(ca_layout& L);
 
 }  // namespace ca

@@ -148,3 +148,83 @@ def test_unsupported_shapes_rejected_before_any_device_work():
     assert "bf16" in ca.compact_attn_last_error()
     assert lib.compact_attn_forward(addr + 1, addr + 16, addr + 32, lay.handle, addr, None) == binding.CA_ERR_INVALID_ARG
     assert lib.compact_attn_forward(addr, addr + 16, addr + 32, lay.handle, addr, None) == binding.CA_ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------- import, union, similarity
+
+def _random_masks(rng, num_heads, n, density):
+    m = rng.random((num_heads, n, n)) < density
+    m[:, :, 0] |= ~m.any(axis=2)            # no empty rows in this helper
+    return m
+
+
+def test_layout_from_csr_roundtrip_and_order():
+    rng = np.random.default_rng(11)
+    T, H, W, tile, n_text, Hd = 3, 9, 10, (1, 4, 4), 16, 3
+    g = Geometry(T, H, W, *tile, n_text)
+    masks = _random_masks(rng, Hd, g.n, 0.3)
+    masks[1, 5] = False                       # an empty row is a legal mask
+    csr = [OL.csr_of_mask(masks[h]) for h in range(Hd)]
+    lay = ca.compact_attn_layout_from_csr(T, H, W, tile, n_text, 1, Hd, 8, "f32", csr)
+    assert lay.n_tiles == g.n and lay.nnz_total == int(masks.sum())
+    for h in range(Hd):
+        rp, ci = ca.compact_attn_layout_csr(lay, h)
+        assert np.array_equal(rp, csr[h][0]) and np.array_equal(ci, csr[h][1])
+        assert np.array_equal(OL.mask_of_csr(g.n, rp, ci), masks[h])
+    assert np.array_equal(ca.compact_attn_layout_order(lay), OL.work_order(masks.sum(axis=2)))
+    # importing what the builder produced gives the builder's layout back
+    wl = get_workload("cfg2")
+    built = build_layout(ca, wl)
+    again = ca.compact_attn_layout_from_csr(wl.T, wl.H, wl.W, wl.tile, wl.n_text, wl.batch, wl.num_heads, wl.head_dim,
+                                            wl.dtype, [ca.compact_attn_layout_csr(built, h) for h in range(wl.num_heads)])
+    for h in range(wl.num_heads):
+        a, b = ca.compact_attn_layout_csr(built, h), ca.compact_attn_layout_csr(again, h)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    assert np.array_equal(ca.compact_attn_layout_order(built), ca.compact_attn_layout_order(again))
+
+
+def test_layout_from_csr_rejects_malformed_input():
+    args = (1, 8, 8, (1, 4, 4), 0, 1, 1, 8, "f32")       # n = 4
+    ok = (np.array([0, 1, 2, 3, 4]), np.array([0, 1, 2, 3]))
+    ca.compact_attn_layout_from_csr(*args, [ok]).free()
+    bad = [
+        (np.array([1, 1, 2, 3, 4]), np.array([0, 1, 2, 3])),      # row_ptr[0] != 0
+        (np.array([0, 2, 1, 3, 4]), np.array([0, 1, 2, 3])),      # decreasing offsets
+        (np.array([0, 2, 2, 3, 4]), np.array([1, 0, 2, 3])),      # unsorted row
+        (np.array([0, 2, 2, 3, 4]), np.array([1, 1, 2, 3])),      # duplicate
+        (np.array([0, 1, 2, 3, 4]), np.array([0, 1, 2, 4])),      # id out of range
+        (np.array([0, 1, 2, 3, 4]), np.array([0, -1, 2, 3])),     # negative id
+    ]
+    for csr in bad:
+        with pytest.raises(ca.CompactAttnError) as e:
+            ca.compact_attn_layout_from_csr(*args, [csr])
+        assert e.value.status == binding.CA_ERR_INVALID_ARG
+
+
+def test_union_and_similarity_match_the_mask_algebra():
+    """Union of configurations (Sec. 4.2) and Sim of Eq. 3 against the oracle's boolean masks."""
+    T, H, W, tile, n_text = 4, 12, 12, (1, 4, 4), 16
+    g = Geometry(T, H, W, *tile, n_text)
+    heads_a = [[(1, (1, 1), ABSENT)], [(3, (0, 2), (2, 0))], []]
+    heads_b = [[(0, (2, 2), ABSENT), (3, (0, 0), ABSENT)], [(3, (0, 2), (2, 0))], [(3, (2, 2), ABSENT)]]
+    la = ca.compact_attn_build_layout(T, H, W, tile, n_text, 1, 3, 8, "f32", heads_a)
+    lb = ca.compact_attn_build_layout(T, H, W, tile, n_text, 1, 3, 8, "f32", heads_b)
+    ma, mb = OL.keep_mask_bruteforce(g, heads_a), OL.keep_mask_bruteforce(g, heads_b)
+    lu = ca.compact_attn_layout_union(la, lb)
+    for h in range(3):
+        rp, ci = ca.compact_attn_layout_csr(lu, h)
+        assert np.array_equal(OL.mask_of_csr(g.n, rp, ci), OL.union_masks(ma[h], mb[h]))
+        for h2 in range(3):
+            assert ca.compact_attn_layout_similarity(la, h, lb, h2) == pytest.approx(OL.mask_similarity(ma[h], mb[h2]), abs=1e-15)
+    assert np.array_equal(ca.compact_attn_layout_order(lu), OL.work_order(OL.union_masks(ma, mb).sum(axis=2)))
+    # closed forms: a mask against itself, against its union, disjoint masks
+    assert ca.compact_attn_layout_similarity(la, 1, lb, 1) == 1.0
+    assert ca.compact_attn_layout_similarity(la, 0, lu, 0) == pytest.approx(ma[0].sum() / (ma[0] | mb[0]).sum())
+    n = g.n
+    eye = [OL.csr_of_mask(np.eye(n, dtype=bool))]
+    off = [OL.csr_of_mask(np.roll(np.eye(n, dtype=bool), 1, axis=1))]
+    le = ca.compact_attn_layout_from_csr(T, H, W, tile, n_text, 1, 1, 8, "f32", eye)
+    lo = ca.compact_attn_layout_from_csr(T, H, W, tile, n_text, 1, 1, 8, "f32", off)
+    assert ca.compact_attn_layout_similarity(le, 0, lo, 0) == 0.0
+    with pytest.raises(ca.CompactAttnError):
+        ca.compact_attn_layout_union(la, le)             # different head counts

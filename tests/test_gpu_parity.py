@@ -265,6 +265,38 @@ def test_rising_and_huge_scores(shape):
         _say(what, compare(to_f64(out[0]), want, *tolerances(dtype), what=what))
 
 
+# ---------------------------------------------------------------- imported and merged masks
+
+@pytest.mark.parametrize("shape", [("bf16", 128, (2, 8, 8)), ("bf16", 128, (1, 8, 8)), ("f32", 64, (1, 4, 4))])
+def test_imported_random_mask_and_union(shape):
+    """An arbitrary tile mask given as CSR, and the union of two layouts, run through the same
+    kernels and match the oracle's definition evaluated on the boolean masks."""
+    dtype, D, tile = shape
+    _say("imported mask", shape)
+    T, H, W = 5, 13, 20
+    B = tile[0] * tile[1] * tile[2]
+    Hd = 3
+    wl = make_workload("import", T, H, W, tile, B, Hd, D, dtype, [[]] * Hd)
+    g = geometry_of(wl)
+    rng = np.random.default_rng(5)
+    masks = rng.random((Hd, g.n, g.n)) < 0.25
+    masks[0, 3] = False                                   # an empty row gives zeros
+    masks[1, :, g.n - 1] = True
+    lay = ca.compact_attn_layout_from_csr(T, H, W, tile, B, 1, Hd, D, dtype, [OL.csr_of_mask(m) for m in masks])
+    q, k, v = make_qkv(wl, DEV)
+    out, _ = gpu_attention(ca, wl, lay, q, k, v)
+    torch.cuda.synchronize()
+    want = OA.tile_mask_attention(g, masks, to_f64(q[0]), to_f64(k[0]), to_f64(v[0]))
+    _say(compare(to_f64(out[0]), want, *tolerances(dtype), what="imported mask"))
+    other = rng.random((Hd, g.n, g.n)) < 0.1
+    lay_b = ca.compact_attn_layout_from_csr(T, H, W, tile, B, 1, Hd, D, dtype, [OL.csr_of_mask(m) for m in other])
+    merged = ca.compact_attn_layout_union(lay, lay_b)
+    out, _ = gpu_attention(ca, wl, merged, q, k, v)
+    torch.cuda.synchronize()
+    want = OA.tile_mask_attention(g, OL.union_masks(masks, other), to_f64(q[0]), to_f64(k[0]), to_f64(v[0]))
+    _say(compare(to_f64(out[0]), want, *tolerances(dtype), what="merged mask"))
+
+
 # ---------------------------------------------------------------- determinism
 
 def test_run_to_run_bitwise_identical():

@@ -157,3 +157,23 @@ def test_row_without_keys_yields_zeros():
     head = [(0, ABSENT, ABSENT)]
     q, k, v = _rand_qkv(g, 1, 4, seed=9)
     assert np.all(A.masked_attention(g, [head], q, k, v) == 0)
+
+
+def test_tile_mask_attention_agrees_with_the_head_rule_and_with_dense():
+    """The mask-driven form of the definition: on a head-described layout it must equal
+    masked_attention, on the all-ones mask the textbook dense softmax, on the identity mask
+    per-tile attention."""
+    g = Geometry(3, 6, 7, 1, 4, 4, 16)
+    heads = [[(1, (0, 1), (1, 0))], [(2, (1, 1), ABSENT)]]
+    rng = np.random.default_rng(3)
+    q, k, v = (rng.standard_normal((2, g.N_real, 8)) for _ in range(3))
+    masks = L.keep_mask_bruteforce(g, heads)
+    assert np.allclose(A.tile_mask_attention(g, masks, q, k, v), A.masked_attention(g, heads, q, k, v), atol=1e-13)
+    ones = np.ones((2, g.n, g.n), dtype=bool)
+    assert np.allclose(A.tile_mask_attention(g, ones, q, k, v), A.dense_attention(q, k, v), atol=1e-13)
+    eye = np.broadcast_to(np.eye(g.n, dtype=bool), (2, g.n, g.n))
+    got = A.tile_mask_attention(g, eye, q, k, v)
+    tok_tile, _ = g.token_tile_and_slot()
+    for t in (0, g.n // 2, g.n - 1):
+        idx = np.nonzero(tok_tile == t)[0]
+        assert np.allclose(got[:, idx], A.dense_attention(q[:, idx], k[:, idx], v[:, idx]), atol=1e-13)

@@ -171,3 +171,18 @@ def test_mask_similarity_closed_forms():
     assert L.mask_similarity(a, a) == 1.0
     assert L.mask_similarity(a, ~a) == 0.0
     assert L.mask_similarity(a, b) == pytest.approx(4 / 12)
+
+
+def test_mask_csr_conversions_and_union():
+    g = Geometry(2, 6, 6, 1, 2, 2, 4)
+    heads = [[(1, (1, 0), (0, 1))], [(0, (2, 2), (-1, -1))]]
+    masks = L.keep_mask_bruteforce(g, heads)
+    csr = L.build_csr(g, heads)
+    for h in range(2):
+        rp, ci = L.csr_of_mask(masks[h])
+        assert np.array_equal(rp, csr[h][0]) and np.array_equal(ci, csr[h][1])
+        assert np.array_equal(L.mask_of_csr(g.n, rp, ci), masks[h])
+    u = L.union_masks(masks[0], masks[1])
+    assert u.sum() == masks[0].sum() + masks[1].sum() - (masks[0] & masks[1]).sum()
+    assert np.all(u >= masks[0]) and np.all(u >= masks[1])
+    assert L.mask_similarity(masks[0], u) == masks[0].sum() / u.sum()
