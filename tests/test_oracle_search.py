@@ -1,0 +1,68 @@
+"""Pins for the oracle's tile mass and recall: closed forms and brute force."""
+import numpy as np
+
+from oracle.geometry import Geometry
+from oracle import attention as A
+from oracle import layout as L
+from oracle import search as S
+
+ABSENT = (-1, -1)
+
+
+def _tokens_per_tile(g):
+    tok_tile, _ = g.token_tile_and_slot()
+    return np.bincount(tok_tile, minlength=g.n)
+
+
+def test_rows_sum_to_tile_population_and_full_mask_has_recall_one():
+    g = Geometry(3, 5, 7, 1, 4, 4, 16)          # padded H and W, one text tile
+    rng = np.random.default_rng(0)
+    q, k = rng.standard_normal((2, g.N_real, 8))
+    m = S.tile_mass(g, q, k)
+    assert m.shape == (g.n, g.n) and np.all(m >= 0)
+    assert np.allclose(m.sum(axis=1), _tokens_per_tile(g), atol=1e-10)
+    assert abs(S.mask_recall(m, np.ones((g.n, g.n), bool)) - 1.0) < 1e-12
+    assert S.mask_recall(m, np.zeros((g.n, g.n), bool)) == 0.0
+
+
+def test_zero_queries_spread_mass_by_population():
+    """Q = 0 makes every row of P uniform: mass[a, b] = |a| * |b| / N_real."""
+    g = Geometry(2, 6, 5, 1, 4, 4, 0)
+    rng = np.random.default_rng(1)
+    k = rng.standard_normal((g.N_real, 8))
+    m = S.tile_mass(g, np.zeros_like(k), k)
+    pop = _tokens_per_tile(g)
+    assert np.allclose(m, np.outer(pop, pop) / g.N_real, atol=1e-12)
+
+
+def test_brute_force_on_a_tiny_grid_and_transposition_sensitivity():
+    g = Geometry(1, 4, 4, 1, 2, 2, 0)
+    rng = np.random.default_rng(2)
+    q, k = rng.standard_normal((2, g.N_real, 4))
+    tok_tile, _ = g.token_tile_and_slot()
+    scale = 4 ** -0.5
+    want = np.zeros((g.n, g.n))
+    for i in range(g.N_real):
+        s = [scale * float(np.dot(q[i], k[j])) for j in range(g.N_real)]
+        mx = max(s)
+        e = [np.exp(x - mx) for x in s]
+        z = sum(e)
+        for j in range(g.N_real):
+            want[tok_tile[i], tok_tile[j]] += e[j] / z
+    got = S.tile_mass(g, q, k)
+    assert np.allclose(got, want, atol=1e-13)
+    assert not np.allclose(got, got.T, atol=1e-3)           # a transposed operand would show
+
+
+def test_recall_of_a_layout_equals_the_kept_probability():
+    """Recall from the mass matrix equals the kept probability summed token by token."""
+    g = Geometry(2, 6, 6, 1, 2, 2, 4)
+    heads = [[(1, (1, 0), (0, 1))]]
+    rng = np.random.default_rng(3)
+    q, k = 1.5 * rng.standard_normal((2, g.N_real, 8))
+    mask = L.keep_mask_bruteforce(g, heads)[0]
+    m = S.tile_mass(g, q, k)
+    tok_tile, _ = g.token_tile_and_slot()
+    p = A.softmax_rows(8 ** -0.5 * (q @ k.T))
+    kept = mask[tok_tile][:, tok_tile]
+    assert abs(S.mask_recall(m, mask) - p[kept].sum() / g.N_real) < 1e-12
