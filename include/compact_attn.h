@@ -162,6 +162,17 @@ int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout*
 int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
                        void* stream);
 
+/* Attention mass per tile pair (Sec. 4.2: masks are searched by the recall they keep, the share of
+ * the full attention's probability mass that falls on kept tile pairs).
+ *   q, k   device pointers, [batch, heads, N_pad, D] in tile order (as for compact_attn_forward).
+ *   mass   device pointer, float32 [batch, heads, n, n], written in full:
+ *          mass[b, h, a, c] = sum over real query tokens i of tile a and real key tokens j of tile c of
+ *          softmax_j(scale * q_i . k_j), the softmax taken over ALL real keys (full attention; the
+ *          windows of the layout are ignored, only its geometry and scale are used).
+ * Row a of mass sums to the number of real tokens of tile a.  Costs as many FLOPs as one dense pass.
+ * Supported: bf16 with (B, D) in {64,128} x {64,128}; otherwise CA_ERR_UNSUPPORTED. */
+int compact_attn_tile_mass(const void* q, const void* k, ca_layout* layout, float* mass, void* stream);
+
 /* Message of the last failure on the calling thread ("" if none); valid until the next call. */
 const char* compact_attn_last_error(void);
 

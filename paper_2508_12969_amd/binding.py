@@ -35,6 +35,7 @@ EXPORTED = (
     "compact_attn_permute",
     "compact_attn_forward",
     "compact_attn_dense",
+    "compact_attn_tile_mass",
     "compact_attn_last_error",
 )
 
@@ -101,6 +102,7 @@ def load_library():
     lib.compact_attn_permute.argtypes = [vp, vp, vp, i32, vp]
     lib.compact_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_dense.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.compact_attn_tile_mass.argtypes = [vp, vp, vp, vp, vp]
     lib.compact_attn_last_error.argtypes = []
     lib.compact_attn_last_error.restype = ctypes.c_char_p
     for name in EXPORTED:
@@ -275,6 +277,21 @@ def _attention(fn, q, k, v, layout, out, stream):
 def compact_attn_forward(q, k, v, layout, out=None, stream=None):
     """Sparse attention over tile-ordered, padded q/k/v [batch, heads, N_pad, D]."""
     return _attention(load_library().compact_attn_forward, q, k, v, layout, out, stream)
+
+
+def compact_attn_tile_mass(q, k, layout, out=None, stream=None):
+    """q, k: tile-ordered padded device tensors -> float32 [batch, heads, n, n] attention mass per tile pair."""
+    import torch
+    _check_tensor(q, layout, True, "q")
+    _check_tensor(k, layout, True, "k")
+    p = layout.problem
+    shape = (p.batch, p.num_heads, layout.n_tiles, layout.n_tiles)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=q.device)
+    elif tuple(out.shape) != shape or out.dtype != torch.float32 or not out.is_contiguous() or out.device != q.device:
+        raise ValueError(f"out must be a contiguous float32 tensor of shape {shape} on {q.device}")
+    _check(load_library().compact_attn_tile_mass(q.data_ptr(), k.data_ptr(), layout.handle, out.data_ptr(), _stream_ptr(stream)))
+    return out
 
 
 def compact_attn_dense(q, k, v, layout, out=None, stream=None):

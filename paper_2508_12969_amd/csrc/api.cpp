@@ -340,6 +340,35 @@ int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* L
   return run_attention(q, k, v, L, out, stream, true);
 }
 
+int compact_attn_tile_mass(const void* q, const void* k, ca_layout* L, float* mass, void* stream) {
+  ca::clear_error();
+  if (!q || !k || !L || !mass) return fail(CA_ERR_INVALID_ARG, "null argument");
+  if (!aligned16(q) || !aligned16(k)) return fail(CA_ERR_INVALID_ARG, "q and k must be 16-byte aligned");
+  const ca_problem& p = L->prob;
+  if (p.dtype != CA_BF16 || !((L->B == 64 || L->B == 128) && (p.head_dim == 64 || p.head_dim == 128))) {
+    set_error("tile mass supports bf16 with tile sizes 64/128 and head_dim 64/128; got dtype=%d B=%lld D=%d", p.dtype,
+              (long long)L->B, p.head_dim);
+    return CA_ERR_UNSUPPORTED;
+  }
+  const int st = ensure_uploaded(L);
+  if (st != CA_OK) return st;
+  ca::MassArgs a{};
+  a.q = q;
+  a.k = k;
+  a.mass = mass;
+  a.tile_class = L->dev.tile_class;
+  a.class_mask = L->dev.class_mask;
+  a.batch = p.batch;
+  a.num_heads = p.num_heads;
+  a.n = L->n;
+  a.B = (int32_t)L->B;
+  a.D = p.head_dim;
+  a.scale = L->scale;
+  const hipError_t e = ca::launch_tile_mass(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "tile mass launch");
+  return CA_OK;
+}
+
 const char* compact_attn_last_error(void) { return ca::last_error(); }
 
 }  // extern "C"

@@ -41,4 +41,18 @@ hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
 // bf16 problems, (B, D) in {64,128} x {64,128}
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
 
+struct MassArgs {
+  const void* q;               // [batch, heads, N_pad, D] tile order, bf16
+  const void* k;
+  float* mass;                 // [batch, heads, n, n]
+  const int32_t* tile_class;   // device [n]
+  const SlotMask* class_mask;  // device
+  int32_t batch, num_heads;
+  int64_t n;
+  int32_t B, D;
+  float scale;
+};
+// bf16 problems, (B, D) in {64,128} x {64,128}
+hipError_t launch_tile_mass(const MassArgs& a, hipStream_t stream);
+
 }  // namespace ca

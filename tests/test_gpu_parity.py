@@ -297,6 +297,51 @@ def test_imported_random_mask_and_union(shape):
     _say(compare(to_f64(out[0]), want, *tolerances(dtype), what="merged mask"))
 
 
+# ---------------------------------------------------------------- attention mass per tile pair
+
+MASS_ABS = 2e-4      # per tile pair, in units of "query tokens": a pair sums up to 128*128 probabilities in
+                     # fp32 from fp32 scores of the same bf16 inputs; exp2 and the sums carry ~1e-6 relative
+                     # error on masses of O(10), measured 1e-6 .. 1.2e-5
+
+
+@pytest.mark.parametrize("shape", [(128, (2, 8, 8), 5, 13, 20, 128), (64, (2, 8, 8), 4, 16, 16, 0),
+                                   (128, (1, 8, 8), 3, 13, 20, 64), (64, (1, 8, 8), 2, 16, 24, 0)])
+def test_tile_mass_matches_the_definition(shape):
+    from oracle import search as OS
+    D, tile, T, H, W, n_text = shape
+    _say("tile mass", shape)
+    Hd = 2
+    wl = make_workload("mass", T, H, W, tile, n_text, Hd, D, "bf16", [[]] * Hd)
+    g = geometry_of(wl)
+    lay = build_layout(ca, wl)
+    for gain in (1.0, 3.0):
+        q, k, _ = make_qkv(wl, DEV, q_gain=gain)
+        qp, kp = ca.compact_attn_permute(q, lay), ca.compact_attn_permute(k, lay)
+        mass = ca.compact_attn_tile_mass(qp, kp, lay)
+        again = ca.compact_attn_tile_mass(qp, kp, lay)
+        torch.cuda.synchronize()
+        assert torch.equal(mass, again)                              # fixed summation order
+        got = mass[0].double().cpu().numpy()
+        tok_tile, _ = g.token_tile_and_slot()
+        pop = np.bincount(tok_tile, minlength=g.n)
+        assert np.allclose(got.sum(axis=2), pop[None, :].repeat(Hd, 0), atol=1e-2)   # rows sum to tile populations
+        for h in range(Hd):
+            want = OS.tile_mass(g, to_f64(q[0, h]), to_f64(k[0, h]))
+            err = np.abs(got[h] - want)
+            _say("head", h, "gain", gain, "max err", err.max(), "max mass", want.max())
+            assert err.max() <= MASS_ABS
+
+
+def test_tile_mass_rejects_fp32():
+    wl = make_workload("massf", 2, 8, 8, (1, 4, 4), 0, 1, 64, "f32", [[]])
+    lay = build_layout(ca, wl)
+    q, k, _ = make_qkv(wl, DEV)
+    qp, kp = ca.compact_attn_permute(q, lay), ca.compact_attn_permute(k, lay)
+    with pytest.raises(ca.CompactAttnError) as e:
+        ca.compact_attn_tile_mass(qp, kp, lay)
+    assert e.value.status == -2
+
+
 # ---------------------------------------------------------------- determinism
 
 def test_run_to_run_bitwise_identical():
