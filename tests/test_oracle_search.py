@@ -66,3 +66,61 @@ def test_recall_of_a_layout_equals_the_kept_probability():
     p = A.softmax_rows(8 ** -0.5 * (q @ k.T))
     kept = mask[tok_tile][:, tok_tile]
     assert abs(S.mask_recall(m, mask) - p[kept].sum() / g.N_real) < 1e-12
+
+
+# ---------------------------------------------------------------- mask search (Sec. 4.2)
+
+def _unit_tiles(nT, nH, nW):
+    return Geometry(nT, nH, nW, 1, 1, 1, 0)             # one token per tile: masses are easy to write down
+
+
+def _coords(g):
+    return np.unravel_index(np.arange(g.n), (g.nT, g.nH, g.nW))
+
+
+def test_search_recovers_a_local_window_and_drops_far_frames():
+    g = _unit_tiles(4, 6, 8)
+    t, h, w = _coords(g)
+    keep = (np.abs(t[:, None] - t) <= 1) & (np.abs(h[:, None] - h) <= 1) & (np.abs(w[:, None] - w) <= 2)
+    mass = keep / keep.sum(axis=1, keepdims=True)
+    groups, recall, kept = S.search_head(g, mass, [0, 1, 3], 1.0 - 1e-12, 0.5)
+    assert groups == [(0, (1, 2), ABSENT), (1, (1, 2), ABSENT), (3, ABSENT, ABSENT)]
+    assert abs(recall - 1.0) < 1e-12
+    assert kept == keep.sum() / g.n ** 2
+
+
+def test_search_recovers_a_cross_as_two_windows():
+    g = _unit_tiles(2, 6, 8)
+    t, h, w = _coords(g)
+    keep = (h[:, None] == h) | (w[:, None] == w)
+    mass = keep / keep.sum(axis=1, keepdims=True)
+    groups, recall, kept = S.search_head(g, mass, [1], 1.0 - 1e-12, 0.5)
+    assert groups == [(1, (0, 7), (5, 0))]
+    assert abs(recall - 1.0) < 1e-12 and kept == keep.sum() / g.n ** 2
+
+
+def test_uniform_attention_is_left_alone_and_thresholds_bind():
+    g = _unit_tiles(3, 4, 5)
+    mass = np.full((g.n, g.n), 1.0 / g.n)
+    groups, recall, kept = S.search_head(g, mass, [0, 2], 0.5, 0.9)      # every move has ratio 1 > lambda
+    assert groups == [(0, (3, 4), ABSENT), (2, (3, 4), ABSENT)] and recall == 1.0 and kept == 1.0
+    groups, recall, kept = S.search_head(g, mass, [0, 2], 0.75, 2.0)     # now only tau stops it
+    assert 0.75 <= recall < 1.0 and abs(recall - kept) < 1e-12           # uniform: recall == kept share
+
+
+def test_reported_recall_equals_the_recall_of_the_built_mask():
+    """The search's own bookkeeping (folded offsets, clipped windows, frame groups) against the
+    layout rule: build the mask from the groups it returns and measure its recall directly."""
+    g = Geometry(5, 9, 7, 1, 2, 2, 0)                   # 5 x 5 x 4 tiles
+    rng = np.random.default_rng(4)
+    q, k = rng.standard_normal((2, g.N_real, 8))
+    q *= 3.0
+    k += 0.8 * np.repeat(rng.standard_normal((g.N_real // 7 + 1, 8)), 7, axis=0)[:g.N_real]
+    mass = S.tile_mass(g, q, k)
+    for tau, lam in ((0.9, 0.5), (0.6, 1.5), (0.99, 0.2)):
+        groups, recall, kept = S.search_head(g, mass, [0, 1, 4], tau, lam)
+        mask = L.keep_mask_bruteforce(g, [groups])[0]
+        assert abs(S.mask_recall(mass, mask) - recall) < 1e-12
+        assert abs(mask.sum() / g.n ** 2 - kept) < 1e-12
+        assert recall >= tau
+        assert all(a[0] <= b[0] and a[1] >= b[1] for _, a, b in groups if b != ABSENT)   # wide / tall roles
