@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--mass-calls", type=int, default=2, help="timed calls of the tile-mass kernel (0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also time the forward kernel on the other cfg4 sparsities")
     return ap.parse_args()
 
@@ -193,6 +194,25 @@ def main():
             ts.append(a.elapsed_time(b))
         dense_ms = sorted(ts)[len(ts) // 2]
 
+    mass = None
+    if args.mass_calls > 0 and wl.dtype == "bf16":
+        # offline step of the method (Sec. 4.2): attention mass per tile pair, two QK^T walks per row
+        m_out = ca.compact_attn_tile_mass(qp, kp, lay)
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(args.mass_calls):
+            a, b = ev(), ev()
+            a.record()
+            ca.compact_attn_tile_mass(qp, kp, lay, out=m_out)
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        mass_ms = sorted(ts)[len(ts) // 2]
+        mass = {"ms": mass_ms, "tflops": dense_flops / mass_ms / 1e9,
+                "pct_bf16_mfma_peak": 100.0 * dense_flops / mass_ms / 1e9 / PEAK_BF16_TFLOPS,
+                "row_sum_error": float((m_out[0].sum(dim=2).sum(dim=1) - lay.n_tokens_real).abs().max())}
+        del m_out
+
     sweep = {}
     if args.sweep:
         for name in ("cfg4-S50", "cfg4-S65", "cfg4-S80"):
@@ -247,6 +267,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "algorithmic_flops_per_launch": flops,
                      "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * lay.n_tokens_padded * D * esz},
+        "tile_mass": mass,
         "cpu_baseline": cpu,
     }
     if sweep:

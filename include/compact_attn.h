@@ -173,6 +173,26 @@ int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* l
  * Supported: bf16 with (B, D) in {64,128} x {64,128}; otherwise CA_ERR_UNSUPPORTED. */
 int compact_attn_tile_mass(const void* q, const void* k, ca_layout* layout, float* mass, void* stream);
 
+/* Window search of one head by boundary contraction (Sec. 4.2), host only.
+ *   layout         any layout of the problem (only its geometry is used).
+ *   mass           host pointer, float32 [n*n]: one head's attention mass per tile pair, row-major
+ *                  (query tile, key tile), e.g. one [n, n] slice of compact_attn_tile_mass copied back.
+ *   group_max_dt   host pointer, num_groups frame-distance boundaries (non-negative, strictly increasing;
+ *                  tile-frame distances beyond the last are dropped, as in ca_head).
+ *   tau, lambda    recall must stay >= tau; a contraction step whose (delta recall / delta cost) exceeds
+ *                  lambda is not taken.  Recall and cost are fractions of the head's video-to-video mass
+ *                  and tile pairs (text tiles are always kept and take no part).
+ *   groups         host pointer, receives num_groups groups (max_dt as given, windows found; both windows
+ *                  absent = the group is dropped), ready to be put in a ca_head.
+ *   recall, kept_fraction   optional outputs: recall and share of video-to-video tile pairs kept.
+ * Starting from full coverage, each group's kept region on folded offsets (|dh|, |dw|) is a box with a
+ * notch at its far corner, i.e. the union of a wide and a tall window (Eq. 2); the cheapest admissible
+ * step over all groups (lower / narrow the box, open / deepen / widen the notch, drop the group) is
+ * applied until none is left.  Errors: CA_ERR_INVALID_ARG, CA_ERR_ALLOC. */
+int compact_attn_search_head(const ca_layout* layout, const float* mass, const int32_t* group_max_dt,
+                             int32_t num_groups, double tau, double lambda, ca_group* groups, double* recall,
+                             double* kept_fraction);
+
 /* Message of the last failure on the calling thread ("" if none); valid until the next call. */
 const char* compact_attn_last_error(void);
 

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     compact_attn_layout_union,
     compact_attn_layout_upload,
     compact_attn_permute,
+    compact_attn_search_head,
     compact_attn_tile_mass,
     library_path,
     load_library,

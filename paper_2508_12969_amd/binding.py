@@ -36,6 +36,7 @@ EXPORTED = (
     "compact_attn_forward",
     "compact_attn_dense",
     "compact_attn_tile_mass",
+    "compact_attn_search_head",
     "compact_attn_last_error",
 )
 
@@ -103,6 +104,9 @@ def load_library():
     lib.compact_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_dense.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_tile_mass.argtypes = [vp, vp, vp, vp, vp]
+    lib.compact_attn_search_head.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32, ctypes.c_double,
+                                             ctypes.c_double, ctypes.POINTER(ca_group), ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_double)]
     lib.compact_attn_last_error.argtypes = []
     lib.compact_attn_last_error.restype = ctypes.c_char_p
     for name in EXPORTED:
@@ -292,6 +296,21 @@ def compact_attn_tile_mass(q, k, layout, out=None, stream=None):
         raise ValueError(f"out must be a contiguous float32 tensor of shape {shape} on {q.device}")
     _check(load_library().compact_attn_tile_mass(q.data_ptr(), k.data_ptr(), layout.handle, out.data_ptr(), _stream_ptr(stream)))
     return out
+
+
+def compact_attn_search_head(layout, mass, group_max_dt, tau, lam):
+    """mass: host float32 [n, n] of one head -> (groups in the head format, recall, kept pair fraction)."""
+    mass = np.ascontiguousarray(mass, dtype=np.float32)
+    if mass.shape != (layout.n_tiles, layout.n_tiles):
+        raise ValueError(f"mass must have shape {(layout.n_tiles, layout.n_tiles)}")
+    G = len(group_max_dt)
+    dts = (ctypes.c_int32 * max(G, 1))(*group_max_dt)
+    groups = (ca_group * max(G, 1))()
+    recall, kept = ctypes.c_double(), ctypes.c_double()
+    _check(load_library().compact_attn_search_head(layout.handle, mass.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), dts, G,
+                                                   float(tau), float(lam), groups, ctypes.byref(recall), ctypes.byref(kept)))
+    out = [(g.max_dt, (g.a.rh, g.a.rw), (g.b.rh, g.b.rw)) for g in groups[:G]]
+    return out, recall.value, kept.value
 
 
 def compact_attn_dense(q, k, v, layout, out=None, stream=None):

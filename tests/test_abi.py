@@ -228,3 +228,55 @@ def test_union_and_similarity_match_the_mask_algebra():
     assert ca.compact_attn_layout_similarity(le, 0, lo, 0) == 0.0
     with pytest.raises(ca.CompactAttnError):
         ca.compact_attn_layout_union(la, le)             # different head counts
+
+
+# ---------------------------------------------------------------- window search (host part of Sec. 4.2)
+
+def test_search_head_matches_the_oracle_search():
+    from oracle import search as OS
+    rng = np.random.default_rng(8)
+    cases = [
+        (Geometry(5, 9, 7, 1, 2, 2, 0), [0, 1, 4]),
+        (Geometry(4, 12, 12, 1, 4, 4, 16), [1, 3]),          # one text tile: takes no part
+        (Geometry(6, 8, 8, 2, 4, 4, 0), [0, 2]),             # tt = 2; frame distances beyond 2 are dropped
+    ]
+    for g, dts in cases:
+        q, k = rng.standard_normal((2, g.N_real, 8))
+        q *= 3.0
+        k += 0.8 * np.repeat(rng.standard_normal((g.N_real // 5 + 1, 8)), 5, axis=0)[:g.N_real]
+        mass = OS.tile_mass(g, q, k).astype(np.float32)
+        lay = ca.compact_attn_build_layout(g.T, g.H, g.W, (g.tt, g.th, g.tw), g.n_text, 1, 1, 8, "f32", [[]])
+        for tau, lam in ((0.95, 0.3), (0.8, 0.8), (0.5, 3.0), (1.0, 0.0)):
+            want, want_recall, want_kept = OS.search_head(g, mass, dts, tau, lam)
+            got, recall, kept = ca.compact_attn_search_head(lay, mass, dts, tau, lam)
+            assert got == want, (g, dts, tau, lam)
+            assert recall == pytest.approx(want_recall, abs=1e-12) and kept == pytest.approx(want_kept, abs=1e-15)
+            # and the recall it reports is the recall of the mask the builder makes from its answer
+            built = ca.compact_attn_build_layout(g.T, g.H, g.W, (g.tt, g.th, g.tw), g.n_text, 1, 1, 8, "f32", [got])
+            rp, ci = ca.compact_attn_layout_csr(built, 0)
+            mask = OL.mask_of_csr(g.n, rp, ci)[:g.n_vid, :g.n_vid]
+            m64 = mass.astype(np.float64)[:g.n_vid, :g.n_vid]
+            assert m64[mask].sum() / m64.sum() == pytest.approx(recall, abs=1e-9)
+            assert recall >= tau - 1e-12
+        lay.free()
+
+
+def test_search_head_closed_forms_and_errors():
+    g = Geometry(4, 6, 8, 1, 1, 1, 0)
+    t, h, w = np.unravel_index(np.arange(g.n), (g.nT, g.nH, g.nW))
+    lay = ca.compact_attn_build_layout(4, 6, 8, (1, 1, 1), 0, 1, 1, 8, "f32", [[]])
+    local = (np.abs(t[:, None] - t) <= 1) & (np.abs(h[:, None] - h) <= 1) & (np.abs(w[:, None] - w) <= 2)
+    groups, recall, kept = ca.compact_attn_search_head(lay, local / local.sum(axis=1, keepdims=True), [0, 1, 3], 1.0 - 1e-6, 0.5)
+    assert groups == [(0, (1, 2), ABSENT), (1, (1, 2), ABSENT), (3, ABSENT, ABSENT)]
+    assert kept == pytest.approx(local.sum() / g.n ** 2)
+    cross = (h[:, None] == h) | (w[:, None] == w)
+    groups, recall, kept = ca.compact_attn_search_head(lay, cross / cross.sum(axis=1, keepdims=True), [3], 1.0 - 1e-6, 0.5)
+    assert groups == [(3, (0, 7), (5, 0))] and recall == pytest.approx(1.0, abs=1e-6)
+    uniform = np.full((g.n, g.n), 1.0 / g.n)
+    groups, recall, kept = ca.compact_attn_search_head(lay, uniform, [3], 0.5, 0.9)
+    assert groups == [(3, (5, 7), ABSENT)] and kept == 1.0
+    for bad in (dict(group_max_dt=[2, 1]), dict(group_max_dt=[-1]), dict(tau=1.5), dict(lam=-1.0), dict(group_max_dt=[])):
+        kw = dict(group_max_dt=[3], tau=0.9, lam=0.5)
+        kw.update(bad)
+        with pytest.raises(ca.CompactAttnError):
+            ca.compact_attn_search_head(lay, uniform, kw["group_max_dt"], kw["tau"], kw["lam"])

@@ -342,6 +342,38 @@ def test_tile_mass_rejects_fp32():
     assert e.value.status == -2
 
 
+def test_search_pipeline_end_to_end():
+    """Mass on the GPU -> window search on the host -> layout -> sparse forward, against the same
+    chain in the oracle: identical windows, recall as reported, outputs within tolerance."""
+    from oracle import search as OS
+    _say("search pipeline")
+    T, H, W, tile, D, Hd = 6, 32, 32, (2, 8, 8), 128, 3
+    wl = make_workload("search", T, H, W, tile, 0, Hd, D, "bf16", [[]] * Hd)
+    g = geometry_of(wl)
+    probe = build_layout(ca, wl)
+    q, k, v = make_qkv(wl, DEV, q_gain=3.0)
+    qp, kp = ca.compact_attn_permute(q, probe), ca.compact_attn_permute(k, probe)
+    mass = ca.compact_attn_tile_mass(qp, kp, probe)
+    torch.cuda.synchronize()
+    mass = mass[0].cpu().numpy()
+    dts, tau, lam = [0, 1, g.nT - 1], 0.9, 0.6
+    heads = []
+    for h in range(Hd):
+        groups, recall, kept = ca.compact_attn_search_head(probe, mass[h], dts, tau, lam)
+        want_mass = OS.tile_mass(g, to_f64(q[0, h]), to_f64(k[0, h]))
+        want_groups, want_recall, _ = OS.search_head(g, want_mass, dts, tau, lam)
+        _say("head", h, groups, "recall", recall, "kept", kept)
+        assert groups == want_groups and abs(recall - want_recall) < 1e-4 and recall >= tau
+        assert kept < 1.0                                   # the position code gives it something to cut
+        heads.append(groups)
+    found = make_workload("found", T, H, W, tile, 0, Hd, D, "bf16", heads)
+    lay = build_layout(ca, found)
+    out, _ = gpu_attention(ca, found, lay, q, k, v)
+    torch.cuda.synchronize()
+    want = OA.masked_attention(g, heads, to_f64(q[0]), to_f64(k[0]), to_f64(v[0]))
+    _say(compare(to_f64(out[0]), want, *tolerances("bf16"), what="searched layout"))
+
+
 # ---------------------------------------------------------------- determinism
 
 def test_run_to_run_bitwise_identical():
