@@ -374,6 +374,33 @@ def test_search_pipeline_end_to_end():
     _say(compare(to_f64(out[0]), want, *tolerances("bf16"), what="searched layout"))
 
 
+# ---------------------------------------------------------------- batch > 1
+
+@pytest.mark.parametrize("dtype,D,tile", [("bf16", 128, (2, 8, 8)), ("bf16", 64, (1, 8, 8)), ("f32", 64, (1, 4, 4))])
+def test_batch_of_three(dtype, D, tile):
+    """Every batch entry is an independent problem with the same layout (rows * batch work items,
+    enough of them here to exercise the XCD-aware remapping of workgroup ids and its remainder)."""
+    import dataclasses
+    _say("batch", dtype, D, tile)
+    B = tile[0] * tile[1] * tile[2]
+    heads = [[(1, (1, 1), ABSENT), (3, (0, 0), ABSENT)], [(5, (0, 3), (2, 0))], []]
+    wl = make_workload("batch", 6, 24, 40, tile, B, len(heads), D, dtype, heads)
+    wl = dataclasses.replace(wl, batch=3)
+    g = geometry_of(wl)
+    lay = build_layout(ca, wl)
+    q, k, v = make_qkv(wl, DEV)
+    out, _ = gpu_attention(ca, wl, lay, q, k, v)
+    dense, _ = gpu_attention(ca, wl, lay, q, k, v, dense=True)
+    torch.cuda.synchronize()
+    assert not torch.equal(out[0], out[1])
+    full = [[(g.nT - 1, (g.nH - 1, g.nW - 1), ABSENT)]] * len(heads)
+    for b in range(3):
+        want = OA.masked_attention(g, heads, to_f64(q[b]), to_f64(k[b]), to_f64(v[b]))
+        _say(b, compare(to_f64(out[b]), want, *tolerances(dtype), what=f"batch {b}"))
+    want = OA.masked_attention(g, full, to_f64(q[2]), to_f64(k[2]), to_f64(v[2]))
+    _say("dense", compare(to_f64(dense[2]), want, *tolerances(dtype), what="dense batch 2"))
+
+
 # ---------------------------------------------------------------- determinism
 
 def test_run_to_run_bitwise_identical():
