@@ -401,6 +401,50 @@ def test_batch_of_three(dtype, D, tile):
     _say("dense", compare(to_f64(dense[2]), want, *tolerances(dtype), what="dense batch 2"))
 
 
+# ---------------------------------------------------------------- streams and graph replay
+
+def test_forward_on_a_side_stream_and_in_a_replayed_graph():
+    """The entry points enqueue on the caller's stream and allocate nothing once the layout is
+    uploaded, so the whole path can be captured in a HIP graph; every replay (with eager work and
+    synchronisation in between) must reproduce the eager result bit for bit."""
+    _say("graph replay")
+    wl = get_workload("cfg2")
+    lay = build_layout(ca, wl)
+    ca.compact_attn_layout_upload(lay)
+    q, k, v = make_qkv(wl, DEV)
+    eager, _ = gpu_attention(ca, wl, lay, q, k, v)
+    torch.cuda.synchronize()
+    shape_p = lay.shape(True)
+    qp, kp, vp, op = (torch.empty(shape_p, dtype=q.dtype, device=DEV) for _ in range(4))
+    out = torch.empty_like(q)
+
+    def path():
+        ca.compact_attn_permute(q, lay, out=qp)
+        ca.compact_attn_permute(k, lay, out=kp)
+        ca.compact_attn_permute(v, lay, out=vp)
+        ca.compact_attn_forward(qp, kp, vp, lay, out=op)
+        ca.compact_attn_permute(op, lay, inverse=True, out=out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        path()
+    side.synchronize()
+    assert torch.equal(out, eager)
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for rep in range(3):
+        out.zero_()
+        op.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep}"
+        _ = (q.float() * 1.0001).sum().item()             # eager work between replays
+
+
 # ---------------------------------------------------------------- determinism
 
 def test_run_to_run_bitwise_identical():
