@@ -129,6 +129,16 @@ int compact_attn_layout_csr(const ca_layout* layout, int32_t head, const int64_t
 /* Host view of the launch order: int32[num_heads*n] of row ids head*n + query_tile. */
 int compact_attn_layout_order(const ca_layout* layout, const int32_t** order);
 
+/* Host view of the query-tile pairs (work ordering of Appendix D's block loop when a workgroup owns
+ * two query tiles and walks the union of their kept lists, used for bf16, 64-token tiles, head_dim
+ * 128): *pairs -> int32[2 * *num_pairs]; entries 2i and 2i+1 are row ids head*n + query_tile of the
+ * two tiles of pair i (same head, neighbours along one grid axis chosen per head so that the unions
+ * are smallest; text tiles pair in id order), the second -1 when a tile has no partner.  Every row
+ * of the layout is in exactly one pair.  Pairs are in launch order: descending union size, ties in
+ * the order (head, first tile id).  *num_pairs is 0 for layouts the paired kernel does not serve.
+ * Owned by the layout, valid until it is freed. */
+int compact_attn_layout_pairs(const ca_layout* layout, const int32_t** pairs, int64_t* num_pairs);
+
 /* Copy the layout's device-side tables (CSR, order, padding masks) to the current HIP device.
  * Synchronous; idempotent.  The compute calls below do it on first use if it was not called.
  * Errors: CA_ERR_ALLOC, CA_ERR_HIP. */

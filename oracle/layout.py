@@ -214,3 +214,51 @@ def union_masks(mask_a, mask_b):
     merged by union, so that every region either of them needs is retained)."""
     return np.logical_or(np.asarray(mask_a, dtype=bool), np.asarray(mask_b, dtype=bool))
 
+
+
+def pair_table(geom: Geometry, masks):
+    """Pairs of query tiles that share a workgroup, in launch order (a scheduling choice of this
+    build, not in the paper; the attention result does not depend on it).
+
+    `masks` is bool[num_heads, n, n].  In every head each video tile with an even coordinate along
+    one grid axis is paired with its neighbour at that coordinate + 1 (no partner at the end of an
+    odd extent); the axis is the one whose pairs have the smallest total union of kept key tiles,
+    among the axes with at least two tiles, tried in the order w, h, t with the first minimum
+    winning (w, all single, if no axis has two tiles).  Text tiles pair up in id order.  The pairs
+    of all heads are sorted by descending union size, ties keeping the order (head, first tile).
+    Returns int32[num_pairs, 2] of row ids head * n + tile, -1 for a missing partner.
+    """
+    masks = np.asarray(masks, dtype=bool)
+    n = geom.n
+    extents = {"w": geom.nW, "h": geom.nH, "t": geom.nT}
+
+    def video_pairs(axis):
+        out = []
+        for t in range(geom.nT):
+            for h in range(geom.nH):
+                for w in range(geom.nW):
+                    c = {"t": t, "h": h, "w": w}
+                    if c[axis] % 2:
+                        continue
+                    first = (t * geom.nH + h) * geom.nW + w
+                    c[axis] += 1
+                    second = (c["t"] * geom.nH + c["h"]) * geom.nW + c["w"] if c[axis] < extents[axis] else -1
+                    out.append((first, second))
+        return out
+
+    def walked(mask, pair):
+        a, b = pair
+        return int(mask[a].sum()) if b < 0 else int(np.logical_or(mask[a], mask[b]).sum())
+
+    entries = []
+    for hd in range(masks.shape[0]):
+        candidates = [ax for ax in ("w", "h", "t") if extents[ax] >= 2] or ["w"]
+        costs = [sum(walked(masks[hd], p) for p in video_pairs(ax)) for ax in candidates]
+        axis = candidates[int(np.argmin(costs))]
+        pairs = video_pairs(axis)
+        for a in range(geom.n_vid, n, 2):
+            pairs.append((a, a + 1 if a + 1 < n else -1))
+        for a, b in pairs:
+            entries.append((walked(masks[hd], (a, b)), hd * n + a, -1 if b < 0 else hd * n + b))
+    order = sorted(range(len(entries)), key=lambda i: -entries[i][0])  # sorted() is stable
+    return np.array([[entries[i][1], entries[i][2]] for i in order], dtype=np.int32).reshape(-1, 2)

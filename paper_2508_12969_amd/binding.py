@@ -30,6 +30,7 @@ EXPORTED = (
     "compact_attn_layout_info",
     "compact_attn_layout_csr",
     "compact_attn_layout_order",
+    "compact_attn_layout_pairs",
     "compact_attn_layout_upload",
     "compact_attn_free_layout",
     "compact_attn_permute",
@@ -97,6 +98,7 @@ def load_library():
     lib.compact_attn_layout_info.argtypes = [vp, i64p, i64p, i64p, i64p, i64p]
     lib.compact_attn_layout_csr.argtypes = [vp, i32, ctypes.POINTER(i64p), ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
     lib.compact_attn_layout_order.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
+    lib.compact_attn_layout_pairs.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)), i64p]
     lib.compact_attn_layout_upload.argtypes = [vp]
     lib.compact_attn_free_layout.argtypes = [vp]
     lib.compact_attn_free_layout.restype = None
@@ -221,6 +223,16 @@ def compact_attn_layout_order(layout):
     o = ctypes.POINTER(ctypes.c_int32)()
     _check(load_library().compact_attn_layout_order(layout.handle, ctypes.byref(o)))
     return np.ctypeslib.as_array(o, shape=(layout.problem.num_heads * layout.n_tiles,)).copy()
+
+
+def compact_attn_layout_pairs(layout):
+    """int32 [num_pairs, 2] of row ids (second -1 for a single), in launch order; empty if unused."""
+    p = ctypes.POINTER(ctypes.c_int32)()
+    count = ctypes.c_int64(0)
+    _check(load_library().compact_attn_layout_pairs(layout.handle, ctypes.byref(p), ctypes.byref(count)))
+    if count.value == 0:
+        return np.zeros((0, 2), dtype=np.int32)
+    return np.ctypeslib.as_array(p, shape=(count.value, 2)).copy()
 
 
 def compact_attn_layout_upload(layout):

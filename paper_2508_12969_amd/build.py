@@ -7,7 +7,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libcompact_attn.so")
-SOURCES = ["layout.cpp", "search.cpp", "api.cpp", "permute.hip", "attn_f32.hip", "attn_bf16.hip", "tile_mass.hip"]
+SOURCES = ["layout.cpp", "search.cpp", "api.cpp", "permute.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_pair.hip",
+           "tile_mass.hip"]
 PER_FILE_FLAGS = {}   # extra hipcc flags for single sources, if any
 ARCH = "gfx950"
 

@@ -51,6 +51,7 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.col_meta) (void)hipFree(d.col_meta);
   if (d.dense_meta) (void)hipFree(d.dense_meta);
   if (d.order) (void)hipFree(d.order);
+  if (d.pair_rows) (void)hipFree(d.pair_rows);
   if (d.tile_class) (void)hipFree(d.tile_class);
   if (d.class_mask) (void)hipFree(d.class_mask);
   d = ca::DeviceTables{};
@@ -98,6 +99,8 @@ int ensure_uploaded(ca_layout* L) {
   if (st == CA_OK) st = upload_vec(col_meta.data(), col_meta.size(), &d.col_meta);
   if (st == CA_OK) st = upload_vec(dense_meta.data(), dense_meta.size(), &d.dense_meta);
   if (st == CA_OK) st = upload_vec(L->order.data(), L->order.size(), &d.order);
+  if (st == CA_OK) st = upload_vec(L->pair_rows.data(), L->pair_rows.size(), &d.pair_rows);
+  d.num_pairs = (int64_t)L->pair_rows.size() / 2;
   if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
   if (st != CA_OK) {
@@ -148,6 +151,8 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   a.row_ptr = dense ? nullptr : L->dev.row_ptr;
   a.col_meta = dense ? L->dev.dense_meta : L->dev.col_meta;
   a.order = dense ? nullptr : L->dev.order;
+  a.pair_rows = L->dev.pair_rows;
+  a.num_pairs = L->dev.num_pairs;
   a.tile_class = L->dev.tile_class;
   a.class_mask = L->dev.class_mask;
   a.batch = L->prob.batch;
@@ -291,6 +296,14 @@ int compact_attn_layout_order(const ca_layout* L, const int32_t** order) {
   ca::clear_error();
   if (!L || !order) return fail(CA_ERR_INVALID_ARG, "null argument");
   *order = L->order.data();
+  return CA_OK;
+}
+
+int compact_attn_layout_pairs(const ca_layout* L, const int32_t** pairs, int64_t* num_pairs) {
+  ca::clear_error();
+  if (!L || !pairs || !num_pairs) return fail(CA_ERR_INVALID_ARG, "null argument");
+  *pairs = L->pair_rows.data();
+  *num_pairs = (int64_t)L->pair_rows.size() / 2;
   return CA_OK;
 }
 

@@ -29,6 +29,8 @@ struct AttnArgs {
   const int64_t* row_ptr;      // device; null selects the dense walk: every row uses col_meta[0..n)
   const int32_t* col_meta;     // device; per kept tile: tile id | padding class << 24
   const int32_t* order;        // device; null = identity
+  const int32_t* pair_rows;    // device [2*num_pairs]; row ids of the two query tiles of a workgroup (-1: none), paired kernel only
+  int64_t num_pairs;
   const int32_t* tile_class;   // device [n]
   const SlotMask* class_mask;  // device
   int32_t batch, num_heads;
@@ -40,6 +42,8 @@ struct AttnArgs {
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
 // bf16 problems, (B, D) in {64,128} x {64,128}
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
+// bf16 problems with B = 64, D = 128: two neighbouring query tiles per workgroup
+hipError_t launch_attn_bf16_pair(const AttnArgs& a, hipStream_t stream);
 
 struct MassArgs {
   const void* q;               // [batch, heads, N_pad, D] tile order, bf16

@@ -156,6 +156,72 @@ void build_order(ca_layout& L) {
 
 }  // namespace
 
+// Pairs of query tiles of one head for the kernel that gives two query tiles to a workgroup, in
+// launch order: pair_rows[2i], pair_rows[2i+1] are row ids head*n + tile, the second -1 for a single.
+static void build_pair_table(ca_layout& L) {
+  std::vector<int32_t>& pair_rows = L.pair_rows;
+  // Partner of a video tile: its neighbour along one grid axis (coordinates 2i and 2i+1; the last
+  // tile of an odd extent stays single).  Which axis costs the fewest walked tiles depends on the
+  // head's windows (a neighbour along an axis in which the windows are wide shares almost all of
+  // its list), so every head takes the axis with the smallest sum of union sizes.  Text tiles pair
+  // up in id order.
+  const int64_t n = L.n;
+  const int32_t ext[3] = {L.nT, L.nH, L.nW};
+  const int64_t stride[3] = {(int64_t)L.nH * L.nW, L.nW, 1};
+  auto union_size = [&](int64_t ra, int64_t rb) {
+    int64_t i = L.row_ptr[ra], ie = L.row_ptr[ra + 1], j = L.row_ptr[rb], je = L.row_ptr[rb + 1], m = 0;
+    while (i < ie && j < je) {
+      const int32_t ti = L.col_idx[i], tj = L.col_idx[j];
+      i += ti <= tj;
+      j += tj <= ti;
+      ++m;
+    }
+    return m + (ie - i) + (je - j);
+  };
+  auto for_pairs = [&](int axis, auto&& visit) {  // visit(tile_a, tile_b or -1) over the video tiles
+    for (int32_t t = 0; t < L.nT; ++t)
+      for (int32_t h = 0; h < L.nH; ++h)
+        for (int32_t w = 0; w < L.nW; ++w) {
+          const int32_t c[3] = {t, h, w};
+          if (c[axis] & 1) continue;
+          const int64_t id = ((int64_t)t * L.nH + h) * L.nW + w;
+          visit(id, c[axis] + 1 < ext[axis] ? id + stride[axis] : (int64_t)-1);
+        }
+  };
+  struct Pair {
+    int32_t a, b;
+    int64_t walked;
+  };
+  std::vector<Pair> pairs;
+  for (int32_t head = 0; head < L.prob.num_heads; ++head) {
+    const int64_t base = (int64_t)head * n;
+    // candidates: the axes with at least two tiles, tried in the order w, h, t; the first of the cheapest wins
+    int best_axis = 2;
+    int64_t best_cost = -1;
+    for (int axis = 2; axis >= 0; --axis) {
+      if (ext[axis] < 2) continue;
+      int64_t cost = 0;
+      for_pairs(axis, [&](int64_t a, int64_t b) {
+        cost += b < 0 ? L.row_ptr[base + a + 1] - L.row_ptr[base + a] : union_size(base + a, base + b);
+      });
+      if (best_cost < 0 || cost < best_cost) best_cost = cost, best_axis = axis;
+    }
+    for_pairs(best_axis, [&](int64_t a, int64_t b) {
+      const int64_t walked = b < 0 ? L.row_ptr[base + a + 1] - L.row_ptr[base + a] : union_size(base + a, base + b);
+      pairs.push_back({(int32_t)(base + a), b < 0 ? -1 : (int32_t)(base + b), walked});
+    });
+    for (int64_t a = L.n_vid; a < n; a += 2) {
+      const bool two = a + 1 < n;
+      const int64_t walked = two ? union_size(base + a, base + a + 1) : L.row_ptr[base + a + 1] - L.row_ptr[base + a];
+      pairs.push_back({(int32_t)(base + a), two ? (int32_t)(base + a + 1) : -1, walked});
+    }
+  }
+  // longest walks first, ties in the order built (head, then tile id)
+  std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& x, const Pair& y) { return x.walked > y.walked; });
+  pair_rows.resize(2 * pairs.size());
+  for (size_t i = 0; i < pairs.size(); ++i) pair_rows[2 * i] = pairs[i].a, pair_rows[2 * i + 1] = pairs[i].b;
+}
+
 void finish_host_tables(ca_layout& L) {
   const int32_t Hd = L.prob.num_heads;
   // per-head relative offsets for the C-ABI view
@@ -167,6 +233,8 @@ void finish_host_tables(ca_layout& L) {
   }
   build_order(L);
   build_slot_masks(L);
+  L.pair_rows.clear();
+  if (L.prob.dtype == CA_BF16 && L.B == 64 && L.prob.head_dim == 128) build_pair_table(L);
 }
 
 int import_host_tables(ca_layout& L, const int64_t* const* row_ptr, const int32_t* const* col_idx) {

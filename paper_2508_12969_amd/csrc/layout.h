@@ -21,6 +21,8 @@ struct DeviceTables {
   int32_t* col_meta = nullptr;   // [nnz] kept key tiles, ascending inside each row: tile id | class << 24
   int32_t* dense_meta = nullptr; // [n] the same packing for the list 0..n-1 (dense walk)
   int32_t* order = nullptr;      // [num_heads*n] launch order of row ids head*n + tile
+  int32_t* pair_rows = nullptr;  // [2*num_pairs] row ids of the two query tiles a workgroup of the paired kernel owns (-1: none), in launch order
+  int64_t num_pairs = 0;
   int32_t* tile_class = nullptr; // [n] index into class_mask; 0 = every slot holds a token
   SlotMask* class_mask = nullptr; // [num_classes]
 };
@@ -38,6 +40,7 @@ struct ca_layout {
   std::vector<int32_t> col_idx;             // [nnz]
   std::vector<std::vector<int64_t>> head_row_ptr;  // per head, relative offsets (C-ABI view)
   std::vector<int32_t> order;               // [num_heads*n]
+  std::vector<int32_t> pair_rows;           // [2*num_pairs], empty unless the paired kernel serves this layout
   std::vector<int32_t> tile_class;          // [n]
   std::vector<ca::SlotMask> class_mask;     // class 0 = all valid
 

@@ -280,3 +280,49 @@ def test_search_head_closed_forms_and_errors():
         kw.update(bad)
         with pytest.raises(ca.CompactAttnError):
             ca.compact_attn_search_head(lay, uniform, kw["group_max_dt"], kw["tau"], kw["lam"])
+
+
+# ---------------------------------------------------------------- query-tile pairs (work ordering of the paired kernel)
+
+@st.composite
+def _pair_cases(draw):
+    tile = draw(st.sampled_from([(1, 8, 8), (2, 4, 8), (4, 4, 4), (1, 4, 16)]))
+    nT, nH, nW = draw(st.integers(1, 4)), draw(st.integers(1, 4)), draw(st.integers(1, 5))
+    T = nT * tile[0] - draw(st.integers(0, tile[0] - 1))
+    H = nH * tile[1] - draw(st.integers(0, tile[1] - 1))
+    W = nW * tile[2] - draw(st.integers(0, tile[2] - 1))
+    n_text = 64 * draw(st.integers(0, 3))
+    win = st.tuples(st.integers(-1, 3), st.integers(-1, 3))
+    heads = []
+    for _ in range(draw(st.integers(1, 3))):
+        k = draw(st.integers(0, 3))
+        dts = sorted(draw(st.sets(st.integers(0, 4), min_size=k, max_size=k)))
+        heads.append([(dt, draw(win), draw(win)) for dt in dts])
+    return T, H, W, tile, n_text, heads
+
+
+@settings(max_examples=60, deadline=None)
+@given(_pair_cases())
+def test_pair_table_bit_exact(case):
+    T, H, W, tile, n_text, heads = case
+    g = Geometry(T, H, W, *tile, n_text)
+    lay = ca.compact_attn_build_layout(T, H, W, tile, n_text, 1, len(heads), 128, "bf16", heads)
+    masks = np.stack([OL.mask_of_csr(g.n, *csr) for csr in OL.build_csr(g, heads)])
+    assert np.array_equal(ca.compact_attn_layout_pairs(lay), OL.pair_table(g, masks))
+    lay.free()
+
+
+def test_pair_table_of_config3_heads_and_absent_elsewhere():
+    wl = get_workload("cfg3")
+    g = geometry_of(wl)
+    picked = [0, 7, 19, 33]
+    heads = [wl.heads[h] for h in picked]
+    lay = ca.compact_attn_build_layout(wl.T, wl.H, wl.W, wl.tile, wl.n_text, 1, len(heads), wl.head_dim, wl.dtype, heads)
+    masks = np.stack([OL.mask_of_csr(g.n, *csr) for csr in OL.build_csr(g, heads)])
+    assert np.array_equal(ca.compact_attn_layout_pairs(lay), OL.pair_table(g, masks))
+    lay.free()
+    # layouts served by the one-tile-per-workgroup kernels carry no pair table
+    for name in ("cfg1", "cfg2"):
+        lay = build_layout(ca, get_workload(name))
+        assert ca.compact_attn_layout_pairs(lay).shape == (0, 2)
+        lay.free()

@@ -282,6 +282,8 @@ def test_imported_random_mask_and_union(shape):
     masks = rng.random((Hd, g.n, g.n)) < 0.25
     masks[0, 3] = False                                   # an empty row gives zeros
     masks[1, :, g.n - 1] = True
+    masks[2, :6] = False                                  # whole pairs of neighbouring rows empty,
+    masks[2, 7] = True                                    # a full row next to sparse ones
     lay = ca.compact_attn_layout_from_csr(T, H, W, tile, B, 1, Hd, D, dtype, [OL.csr_of_mask(m) for m in masks])
     q, k, v = make_qkv(wl, DEV)
     out, _ = gpu_attention(ca, wl, lay, q, k, v)

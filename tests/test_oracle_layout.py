@@ -186,3 +186,69 @@ def test_mask_csr_conversions_and_union():
     assert u.sum() == masks[0].sum() + masks[1].sum() - (masks[0] & masks[1]).sum()
     assert np.all(u >= masks[0]) and np.all(u >= masks[1])
     assert L.mask_similarity(masks[0], u) == masks[0].sum() / u.sum()
+
+
+def _axis_cost_by_reshape(g, mask, axis):
+    """Total union size of the video pairs along one tile-grid axis, computed on the reshaped mask."""
+    n_vid = g.n_vid
+    m = mask[:n_vid].reshape(g.nT, g.nH, g.nW, -1)
+    m = np.moveaxis(m, axis, 0)
+    even, odd = m[0::2], m[1::2]
+    cost = int(np.logical_or(even[:odd.shape[0]], odd).sum())
+    if even.shape[0] > odd.shape[0]:
+        cost += int(even[-1].sum())
+    return cost
+
+
+def test_pair_table_hand_worked():
+    # 2 x 2 tile grid in one frame.  Head 0 keeps a query's own tile row (both columns): tiles 0 and 1
+    # have the same list, so pairing along w walks 2 tiles per pair and pairing along h walks 4.
+    # Head 1 keeps the own column (both rows): the other way round.
+    g = Geometry(1, 16, 16, 1, 8, 8, 0)
+    masks = L.keep_mask_bruteforce(g, [[(0, (0, 1), (-1, -1))], [(0, (1, 0), (-1, -1))]])
+    assert L.pair_table(g, masks).tolist() == [[0, 1], [2, 3], [4, 6], [5, 7]]
+    # 1 x 3 grid plus three text tiles: the odd column and the odd text tile stay single; the text
+    # rows keep all 6 tiles, the video rows their own tile and the text: unions 6, 6, 5 (tiles 0|1), 4
+    g = Geometry(1, 8, 24, 1, 8, 8, 192)
+    masks = L.keep_mask_bruteforce(g, [[(0, (0, 0), (-1, -1))]])
+    assert L.pair_table(g, masks).tolist() == [[3, 4], [5, -1], [0, 1], [2, -1]]
+    # a single tile: nothing to pair with
+    g = Geometry(1, 8, 8, 1, 8, 8, 0)
+    assert L.pair_table(g, np.ones((1, 1, 1), bool)).tolist() == [[0, -1]]
+
+
+def test_pair_table_invariants_on_random_masks():
+    rng = np.random.default_rng(5)
+    for (T, H, W, tile, n_text) in [(3, 16, 24, (1, 8, 8), 64), (4, 8, 8, (2, 4, 8), 0), (5, 12, 4, (4, 4, 4), 128)]:
+        g = Geometry(T, H, W, *tile, n_text)
+        masks = rng.random((3, g.n, g.n)) < 0.3
+        # make the heads prefer different axes: head 0 gets lists that only depend on (h, w), head 1 on (t, w)
+        t_of = np.arange(g.n_vid) // (g.nH * g.nW)
+        hw_of = np.arange(g.n_vid) % (g.nH * g.nW)
+        masks[0, :g.n_vid] = masks[0, hw_of]
+        masks[1, :g.n_vid] = masks[1, (t_of * g.nH * g.nW + hw_of % g.nW)]
+        pairs = L.pair_table(g, masks)
+        rows = pairs[pairs >= 0]
+        assert sorted(rows.tolist()) == list(range(3 * g.n))            # every row exactly once
+        walked = []
+        for a, b in pairs:
+            hd, ta = divmod(int(a), g.n)
+            if b >= 0:
+                assert b // g.n == hd and b > a
+            walked.append(int((masks[hd, ta] | masks[hd, b % g.n]).sum()) if b >= 0 else int(masks[hd, ta].sum()))
+        assert np.all(np.diff(walked) <= 0)                             # longest unions first
+        for hd in range(3):
+            mine = pairs[(pairs[:, 0] // g.n) == hd]
+            video = mine[mine[:, 0] % g.n < g.n_vid]
+            strides = set(int(b - a) for a, b in video if b >= 0)
+            assert len(strides) <= 1                                    # one axis per head
+            cost = sum(w for w, (a, _) in zip(walked, pairs) if a // g.n == hd and a % g.n < g.n_vid)
+            by_axis = [_axis_cost_by_reshape(g, masks[hd], ax) for ax in range(3)
+                       if (g.nT, g.nH, g.nW)[ax] >= 2]
+            assert cost == min(by_axis)                                 # and it is the cheapest one
+        # head 0's lists do not depend on t, so neighbours along t share their list and that axis wins;
+        # head 1's do not depend on h
+        first = {hd: pairs[(pairs[:, 0] // g.n == hd) & (pairs[:, 1] >= 0) & (pairs[:, 0] % g.n < g.n_vid)][0] for hd in (0, 1)}
+        assert int(first[0][1] - first[0][0]) == g.nH * g.nW
+        if g.nH >= 2:
+            assert int(first[1][1] - first[1][0]) == g.nW
