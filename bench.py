@@ -41,6 +41,9 @@ def parse():
                     help="also launch one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--mass-calls", type=int, default=2, help="timed calls of the tile-mass kernel (0 = skip)")
+    ap.add_argument("--pattern-report", action="store_true",
+                    help="also search masks under the three pattern families of Table 3 on structured synthetic heads "
+                         "and report the sparsity each family reaches")
     ap.add_argument("--sweep", action="store_true", help="also time the forward kernel on the other cfg4 sparsities")
     return ap.parse_args()
 
@@ -111,6 +114,42 @@ def cpu_baseline(wl, q, k, v, budget_s):
         "sample": f"{tiles} random (head, query tile) rows of {wl.name} ({pairs} tile pairs) in {dt:.1f} s, "
                   "fp64 numpy incl. host copies; FLOPs counted as for the GPU (4*B^2*D per kept tile pair)",
     }
+
+
+# Head kinds of Sec. 3.2 as gains of the positional code per axis (t, y, x); see workloads/inputs.py
+PATTERN_HEADS = (("local", (2.5, 2.5, 2.5)), ("cross, fading with frame distance", (1.0, 3.0, 3.0)),
+                 ("global", (0.0, 0.0, 0.0)), ("own frame", (3.0, 1.0, 1.0)), ("cross, time-invariant", (0.0, 2.5, 2.5)))
+
+
+def pattern_report(ca, dev, tau=0.9, lam=0.6):
+    """Sparsity reached by the window search under each pattern family (the structure of Table 3: a
+    cubic window, + one window per frame group, + dual windows) on synthetic heads with the same
+    thresholds.  The numbers describe the synthetic heads, not a trained model."""
+    import torch
+    from workloads.configs import Workload
+    from workloads.inputs import make_qkv
+    heads = [[]] * len(PATTERN_HEADS)
+    wl = Workload("patterns", 9, 12, 48, 80, (2, 8, 8), 0, len(heads), 128, "bf16", tuple(heads), None)
+    lay = ca.compact_attn_build_layout(wl.T, wl.H, wl.W, wl.tile, wl.n_text, wl.batch, wl.num_heads, wl.head_dim,
+                                       wl.dtype, wl.heads, 0.0)
+    q, k, _ = make_qkv(wl, dev, axis_gain=[g for _, g in PATTERN_HEADS])
+    mass = ca.compact_attn_tile_mass(ca.compact_attn_permute(q, lay), ca.compact_attn_permute(k, lay), lay)
+    torch.cuda.synchronize()
+    mass = mass[0].cpu().numpy()
+    nT = -(-wl.T // wl.tile[0])
+    bounds = list(range(nT))                      # one group per tile-frame distance
+    out = {"tau": tau, "lambda": lam, "grid_tiles": [nT, -(-wl.H // wl.tile[1]), -(-wl.W // wl.tile[2])], "heads": {}}
+    totals = {p: 0.0 for p in ("cubic", "frame_groups", "dual")}
+    for h, (kind, _) in enumerate(PATTERN_HEADS):
+        row = {}
+        for pattern in totals:
+            _, recall, kept = ca.compact_attn_search_head(lay, mass[h], bounds, tau, lam, pattern)
+            row[pattern] = {"sparsity": 1.0 - kept, "recall": recall}
+            totals[pattern] += (1.0 - kept) / len(PATTERN_HEADS)
+        out["heads"][kind] = row
+    out["overall_sparsity"] = totals
+    lay.free()
+    return out
 
 
 def main():
@@ -262,7 +301,7 @@ def main():
                  "dense_ms": dense_ms, "dense_tflops": (dense_flops / dense_ms / 1e9) if dense_ms else None,
                  "speedup_vs_dense": (dense_ms / fwd_med) if dense_ms else None, "ideal_speedup": 1.0 / kept},
         "permute": {"ms_q_k_v": perm3_avg, "gbps": perm_bytes / perm3_avg / 1e6, "pct_hbm_peak": perm_bytes / perm3_avg / 1e6 / 8000 * 100},
-        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": flops / fwd_avg / 1e9,
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_pair_kernel" if (B, D) == (64, 128) else "attn_bf16_kernel", "achieved": flops / fwd_avg / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "algorithmic_flops_per_launch": flops,
@@ -272,6 +311,8 @@ def main():
     }
     if sweep:
         rec["sweep"] = sweep
+    if args.pattern_report:
+        rec["patterns"] = pattern_report(ca, dev)
     print(json.dumps(rec))
 
 

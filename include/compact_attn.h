@@ -50,6 +50,12 @@ typedef enum {
 
 typedef enum { CA_F32 = 0, CA_BF16 = 1 } ca_dtype;
 
+/* Pattern families a window search may use (the three columns of Table 3), each containing the one
+ * before: a cubic window (one spatial window for every kept frame distance plus a temporal radius),
+ * one window per frame group (Sec. 4.1, frame-group-wise patterns), two windows per frame group
+ * (Sec. 4.1, dual attention windows). */
+typedef enum { CA_PATTERN_CUBIC = 0, CA_PATTERN_FRAME_GROUPS = 1, CA_PATTERN_DUAL = 2 } ca_pattern;
+
 /* One axis-aligned, query-centred window in tile units: key tile (kh,kw) is inside iff
  * |kh-qh| <= rh and |kw-qw| <= rw (Eq. 1).  A negative radius marks the window absent. */
 typedef struct {
@@ -192,6 +198,11 @@ int compact_attn_tile_mass(const void* q, const void* k, ca_layout* layout, floa
  *   tau, lambda    recall must stay >= tau; a contraction step whose (delta recall / delta cost) exceeds
  *                  lambda is not taken.  Recall and cost are fractions of the head's video-to-video mass
  *                  and tile pairs (text tiles are always kept and take no part).
+ *   pattern        ca_pattern: CA_PATTERN_DUAL searches two windows per group as described below;
+ *                  CA_PATTERN_FRAME_GROUPS one window per group (no notch steps: window b is always
+ *                  absent); CA_PATTERN_CUBIC one window shared by the groups 0..k-1 and the groups from
+ *                  k on dropped (steps: lower or narrow the shared window, drop the outermost kept
+ *                  group; with boundaries 0, 1, 2, ... this is a sliding cube of tiles).
  *   groups         host pointer, receives num_groups groups (max_dt as given, windows found; both windows
  *                  absent = the group is dropped), ready to be put in a ca_head.
  *   recall, kept_fraction   optional outputs: recall and share of video-to-video tile pairs kept.
@@ -200,8 +211,8 @@ int compact_attn_tile_mass(const void* q, const void* k, ca_layout* layout, floa
  * step over all groups (lower / narrow the box, open / deepen / widen the notch, drop the group) is
  * applied until none is left.  Errors: CA_ERR_INVALID_ARG, CA_ERR_ALLOC. */
 int compact_attn_search_head(const ca_layout* layout, const float* mass, const int32_t* group_max_dt,
-                             int32_t num_groups, double tau, double lambda, ca_group* groups, double* recall,
-                             double* kept_fraction);
+                             int32_t num_groups, double tau, double lambda, int32_t pattern, ca_group* groups,
+                             double* recall, double* kept_fraction);
 
 /* Message of the last failure on the calling thread ("" if none); valid until the next call. */
 const char* compact_attn_last_error(void);

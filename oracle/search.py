@@ -58,6 +58,12 @@ def mask_recall(mass, mask):
 #     loop: every live group proposes its cheapest admissible move (lowest ratio, ties by the order
 #     A, C, N0, N1, N2, Z); a group without one is finished; the cheapest proposal overall (ties:
 #     lowest group) is applied; the search ends when no group is live.
+#   * Pattern families (the three columns of Table 3), each a restriction of the one before:
+#       "dual"          everything above: per group a pair of windows;
+#       "frame_groups"  per group ONE window: moves A, C and Z only;
+#       "cubic"         one spatial window shared by all kept groups and a temporal radius, the
+#                       sliding-tile cube the table starts from: a single region and the moves A and
+#                       C applied to every kept group at once, Z dropping the outermost kept group.
 # ---------------------------------------------------------------------------------------------
 
 def fold_group_tables(geom: Geometry, mass, group_max_dt):
@@ -130,12 +136,56 @@ class _Region:
 
 
 MOVES = ("A", "C", "N0", "N1", "N2", "Z")
+PATTERNS = ("cubic", "frame_groups", "dual")
 
 
-def search_head(geom: Geometry, mass, group_max_dt, tau, lam):
+def _search_cubic(geom, R, C, lost_mass, lost_pairs, group_max_dt, tau, lam):
+    """One window (h, w) for the groups 0 .. k-1, the rest dropped; greedy over three joint moves."""
+    total_mass = R.sum() + lost_mass
+    total_pairs = int(C.sum()) + lost_pairs
+    G = len(group_max_dt)
+    h, w, k = geom.nH - 1, geom.nW - 1, G
+    recall = float(R.sum() / total_mass) if total_mass > 0 else 1.0
+    kept_pairs = int(C.sum())
+    while k > 0:
+        candidates = []
+        if h > 0:
+            candidates.append(((h - 1, w, k), [(g, h, j) for g in range(k) for j in range(w + 1)]))
+        if w > 0:
+            candidates.append(((h, w - 1, k), [(g, i, w) for g in range(k) for i in range(h + 1)]))
+        candidates.append(((h, w, k - 1), [(k - 1, i, j) for i in range(h + 1) for j in range(w + 1)]))
+        best = None
+        for state, gone in candidates:
+            pairs = sum(int(C[c]) for c in gone)
+            if pairs == 0:
+                continue
+            d_mass = 0.0
+            for c in sorted(gone):
+                d_mass += R[c]
+            d_recall = d_mass / total_mass if total_mass > 0 else 0.0
+            ratio = d_recall / (pairs / total_pairs)
+            if ratio > lam or recall - d_recall < tau:
+                continue
+            if best is None or ratio < best[0]:
+                best = (ratio, state, d_recall, pairs)
+        if best is None:
+            break
+        _, (h, w, k), d_recall, pairs = best
+        recall -= d_recall
+        kept_pairs -= pairs
+    groups = [(int(group_max_dt[g]), (h, w) if g < k else (-1, -1), (-1, -1)) for g in range(G)]
+    return groups, recall, kept_pairs / total_pairs
+
+
+def search_head(geom: Geometry, mass, group_max_dt, tau, lam, pattern="dual"):
     """Returns (groups, recall, kept_pair_fraction): groups as [(max_dt, (rh, rw), (rh, rw)), ...] in the
     head format of oracle.layout, recall and kept fraction over video-to-video tile pairs."""
+    if pattern not in PATTERNS:
+        raise ValueError(f"pattern must be one of {PATTERNS}")
     R, C, lost_mass, lost_pairs = fold_group_tables(geom, mass, group_max_dt)
+    if pattern == "cubic":
+        return _search_cubic(geom, R, C, lost_mass, lost_pairs, group_max_dt, tau, lam)
+    moves = MOVES if pattern == "dual" else ("A", "C", "Z")
     total_mass = R.sum() + lost_mass
     total_pairs = int(C.sum()) + lost_pairs
     G = len(group_max_dt)
@@ -149,7 +199,7 @@ def search_head(geom: Geometry, mass, group_max_dt, tau, lam):
         now = regions[g].cells()
         if regions[g].dropped:
             return None
-        for move in MOVES:
+        for move in moves:
             nxt = regions[g].after(move)
             if nxt is None:
                 continue

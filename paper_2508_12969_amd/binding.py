@@ -107,7 +107,7 @@ def load_library():
     lib.compact_attn_dense.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_tile_mass.argtypes = [vp, vp, vp, vp, vp]
     lib.compact_attn_search_head.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32, ctypes.c_double,
-                                             ctypes.c_double, ctypes.POINTER(ca_group), ctypes.POINTER(ctypes.c_double),
+                                             ctypes.c_double, i32, ctypes.POINTER(ca_group), ctypes.POINTER(ctypes.c_double),
                                              ctypes.POINTER(ctypes.c_double)]
     lib.compact_attn_last_error.argtypes = []
     lib.compact_attn_last_error.restype = ctypes.c_char_p
@@ -310,8 +310,13 @@ def compact_attn_tile_mass(q, k, layout, out=None, stream=None):
     return out
 
 
-def compact_attn_search_head(layout, mass, group_max_dt, tau, lam):
+CA_PATTERNS = {"cubic": 0, "frame_groups": 1, "dual": 2}
+
+
+def compact_attn_search_head(layout, mass, group_max_dt, tau, lam, pattern="dual"):
     """mass: host float32 [n, n] of one head -> (groups in the head format, recall, kept pair fraction)."""
+    if pattern not in CA_PATTERNS:
+        raise ValueError(f"pattern must be one of {tuple(CA_PATTERNS)}")
     mass = np.ascontiguousarray(mass, dtype=np.float32)
     if mass.shape != (layout.n_tiles, layout.n_tiles):
         raise ValueError(f"mass must have shape {(layout.n_tiles, layout.n_tiles)}")
@@ -320,7 +325,8 @@ def compact_attn_search_head(layout, mass, group_max_dt, tau, lam):
     groups = (ca_group * max(G, 1))()
     recall, kept = ctypes.c_double(), ctypes.c_double()
     _check(load_library().compact_attn_search_head(layout.handle, mass.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), dts, G,
-                                                   float(tau), float(lam), groups, ctypes.byref(recall), ctypes.byref(kept)))
+                                                   float(tau), float(lam), CA_PATTERNS[pattern], groups, ctypes.byref(recall),
+                                                   ctypes.byref(kept)))
     out = [(g.max_dt, (g.a.rh, g.a.rw), (g.b.rh, g.b.rw)) for g in groups[:G]]
     return out, recall.value, kept.value
 

@@ -383,7 +383,8 @@ int compact_attn_tile_mass(const void* q, const void* k, ca_layout* L, float* ma
 }
 
 int compact_attn_search_head(const ca_layout* L, const float* mass, const int32_t* group_max_dt, int32_t num_groups,
-                             double tau, double lambda, ca_group* groups, double* recall, double* kept_fraction) {
+                             double tau, double lambda, int32_t pattern, ca_group* groups, double* recall,
+                             double* kept_fraction) {
   ca::clear_error();
   if (!L || !mass || !group_max_dt || !groups) return fail(CA_ERR_INVALID_ARG, "null argument");
   if (num_groups < 1 || num_groups > CA_MAX_GROUPS) return fail(CA_ERR_INVALID_ARG, "num_groups must be in 1..CA_MAX_GROUPS");
@@ -391,8 +392,10 @@ int compact_attn_search_head(const ca_layout* L, const float* mass, const int32_
     if (group_max_dt[g] < 0 || (g > 0 && group_max_dt[g] <= group_max_dt[g - 1]))
       return fail(CA_ERR_INVALID_ARG, "group_max_dt must be non-negative and strictly increasing");
   if (!(tau >= 0.0 && tau <= 1.0) || !(lambda >= 0.0)) return fail(CA_ERR_INVALID_ARG, "tau must lie in [0, 1] and lambda be >= 0");
+  if (pattern != CA_PATTERN_CUBIC && pattern != CA_PATTERN_FRAME_GROUPS && pattern != CA_PATTERN_DUAL)
+    return fail(CA_ERR_INVALID_ARG, "pattern must be a ca_pattern value");
   try {
-    return ca::search_head_windows(*L, mass, group_max_dt, num_groups, tau, lambda, groups, recall, kept_fraction);
+    return ca::search_head_windows(*L, mass, group_max_dt, num_groups, tau, lambda, pattern, groups, recall, kept_fraction);
   } catch (const std::bad_alloc&) {
     return fail(CA_ERR_ALLOC, "out of host memory in the window search");
   }

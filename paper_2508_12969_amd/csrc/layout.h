@@ -67,7 +67,7 @@ int union_host_tables(ca_layout& L, const ca_layout& a, const ca_layout& b);
 double head_similarity(const ca_layout& a, int32_t ha, const ca_layout& b, int32_t hb);
 // Window search of one head (search.cpp); mass is host float [n*n], groups_out has num_groups entries.
 int search_head_windows(const ca_layout& L, const float* mass, const int32_t* group_max_dt, int32_t num_groups, double tau,
-                        double lambda, ca_group* groups_out, double* recall_out, double* kept_out);
+                        double lambda, int32_t pattern, ca_group* groups_out, double* recall_out, double* kept_out);
 // Derived tables (per-head views, launch order, padding classes) once row_ptr / col_idx are set.
 void finish_host_tables(ca_layout& L);
 

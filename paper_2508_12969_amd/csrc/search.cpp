@@ -15,6 +15,10 @@
 //     or drop the group.  A move must remove at least one tile pair, keep recall >= tau and have a
 //     ratio <= lambda.  Every live group proposes its cheapest such move, the cheapest proposal
 //     overall is applied, a group without a proposal is finished.
+//   - Pattern families (the columns of Table 3): dual windows as above; frame groups with one
+//     window each (no notch moves); a cubic window, i.e. one spatial window shared by all kept
+//     groups plus a temporal radius (lower / narrow it in every kept group at once, or drop the
+//     outermost kept group).
 #include <cstdint>
 #include <vector>
 
@@ -75,7 +79,7 @@ struct Proposal {
 }  // namespace
 
 int search_head_windows(const ca_layout& L, const float* mass, const int32_t* group_max_dt, int32_t num_groups, double tau,
-                        double lambda, ca_group* groups_out, double* recall_out, double* kept_out) {
+                        double lambda, int32_t pattern, ca_group* groups_out, double* recall_out, double* kept_out) {
   const int nT = L.nT, nH = L.nH, nW = L.nW;
   const int64_t n = L.n, n_vid = L.n_vid;
   const int G = num_groups;
@@ -124,6 +128,52 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
   const int64_t total_pairs = kept_pairs + lost_pairs;
   double recall = total_mass > 0 ? kept_mass / total_mass : 1.0;
 
+  if (pattern == CA_PATTERN_CUBIC) {
+    int h = nH - 1, w = nW - 1, k = G;
+    while (k > 0) {
+      // the three joint moves in the order lower, narrow, drop outermost; cells visited in ascending (g, i, j)
+      bool have = false;
+      double best_ratio = 0, best_d_recall = 0;
+      int64_t best_pairs = 0;
+      int best_move = -1;
+      for (int move = 0; move < 3; ++move) {
+        if ((move == 0 && h == 0) || (move == 1 && w == 0)) continue;
+        int64_t pairs = 0;
+        double d_mass = 0.0;
+        const int g0 = move == 2 ? k - 1 : 0;
+        for (int g = g0; g < k; ++g)
+          for (int i = (move == 0 ? h : 0); i <= h; ++i)
+            for (int j = (move == 1 ? w : 0); j <= w; ++j) {
+              const size_t cell = ((size_t)g * nH + i) * nW + j;
+              pairs += C[cell];
+              d_mass += R[cell];
+            }
+        if (pairs == 0) continue;
+        const double d_recall = total_mass > 0 ? d_mass / total_mass : 0.0;
+        const double ratio = d_recall / ((double)pairs / (double)total_pairs);
+        if (ratio > lambda || recall - d_recall < tau) continue;
+        if (!have || ratio < best_ratio) have = true, best_ratio = ratio, best_d_recall = d_recall, best_pairs = pairs, best_move = move;
+      }
+      if (!have) break;
+      if (best_move == 0) --h;
+      else if (best_move == 1) --w;
+      else --k;
+      recall -= best_d_recall;
+      kept_pairs -= best_pairs;
+    }
+    for (int g = 0; g < G; ++g) {
+      ca_group out{};
+      out.max_dt = group_max_dt[g];
+      out.a = g < k ? ca_window{h, w} : ca_window{-1, -1};
+      out.b = ca_window{-1, -1};
+      groups_out[g] = out;
+    }
+    if (recall_out) *recall_out = recall;
+    if (kept_out) *kept_out = total_pairs > 0 ? (double)kept_pairs / (double)total_pairs : 1.0;
+    return CA_OK;
+  }
+  const bool notch_moves = pattern == CA_PATTERN_DUAL;
+
   std::vector<Region> regions(G, Region{nH - 1, nH - 1, nW - 1, nW - 1, false});
   std::vector<char> live(G, 1);
   auto propose = [&](int g) {
@@ -132,6 +182,7 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
     if (now.dropped) return best;
     for (int move = 0; move < kNumMoves; ++move) {
       Region nxt;
+      if (!notch_moves && (move == kOpenNotch || move == kDeepenNotch || move == kWidenNotch)) continue;
       if (!apply(now, move, &nxt)) continue;
       int64_t pairs = 0;
       double d_mass = 0.0;

@@ -246,10 +246,11 @@ def test_search_head_matches_the_oracle_search():
         k += 0.8 * np.repeat(rng.standard_normal((g.N_real // 5 + 1, 8)), 5, axis=0)[:g.N_real]
         mass = OS.tile_mass(g, q, k).astype(np.float32)
         lay = ca.compact_attn_build_layout(g.T, g.H, g.W, (g.tt, g.th, g.tw), g.n_text, 1, 1, 8, "f32", [[]])
-        for tau, lam in ((0.95, 0.3), (0.8, 0.8), (0.5, 3.0), (1.0, 0.0)):
-            want, want_recall, want_kept = OS.search_head(g, mass, dts, tau, lam)
-            got, recall, kept = ca.compact_attn_search_head(lay, mass, dts, tau, lam)
-            assert got == want, (g, dts, tau, lam)
+        for tau, lam, pattern in [(t, l, p) for (t, l) in ((0.95, 0.3), (0.8, 0.8), (0.5, 3.0), (1.0, 0.0))
+                                  for p in ("dual", "frame_groups", "cubic")]:
+            want, want_recall, want_kept = OS.search_head(g, mass, dts, tau, lam, pattern)
+            got, recall, kept = ca.compact_attn_search_head(lay, mass, dts, tau, lam, pattern)
+            assert got == want, (g, dts, tau, lam, pattern)
             assert recall == pytest.approx(want_recall, abs=1e-12) and kept == pytest.approx(want_kept, abs=1e-15)
             # and the recall it reports is the recall of the mask the builder makes from its answer
             built = ca.compact_attn_build_layout(g.T, g.H, g.W, (g.tt, g.th, g.tw), g.n_text, 1, 1, 8, "f32", [got])
@@ -275,6 +276,23 @@ def test_search_head_closed_forms_and_errors():
     uniform = np.full((g.n, g.n), 1.0 / g.n)
     groups, recall, kept = ca.compact_attn_search_head(lay, uniform, [3], 0.5, 0.9)
     assert groups == [(3, (5, 7), ABSENT)] and kept == 1.0
+    # the same cross under the narrower families: one window must cover both arms (everything), a cube too
+    for pattern in ("frame_groups", "cubic"):
+        groups, recall, kept = ca.compact_attn_search_head(lay, cross / cross.sum(axis=1, keepdims=True), [3], 1.0 - 1e-6,
+                                                           0.5, pattern)
+        assert groups == [(3, (5, 7), ABSENT)] and kept == 1.0
+    # the local head: per-group windows find it exactly; the cube has one window for the frames it keeps
+    for pattern in ("frame_groups", "cubic"):
+        groups, _, kept = ca.compact_attn_search_head(lay, local / local.sum(axis=1, keepdims=True), [0, 1, 3], 1.0 - 1e-6,
+                                                      0.5, pattern)
+        assert groups == [(0, (1, 2), ABSENT), (1, (1, 2), ABSENT), (3, ABSENT, ABSENT)]
+    with pytest.raises(ca.CompactAttnError):
+        binding.load_library()  # the raw call: a pattern value outside the enum
+        dts = (ctypes.c_int32 * 1)(3)
+        out = (binding.ca_group * 1)()
+        m = np.ascontiguousarray(uniform, dtype=np.float32)
+        binding._check(binding.load_library().compact_attn_search_head(
+            lay.handle, m.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), dts, 1, 0.9, 0.5, 7, out, None, None))
     for bad in (dict(group_max_dt=[2, 1]), dict(group_max_dt=[-1]), dict(tau=1.5), dict(lam=-1.0), dict(group_max_dt=[])):
         kw = dict(group_max_dt=[3], tau=0.9, lam=0.5)
         kw.update(bad)

@@ -376,6 +376,50 @@ def test_search_pipeline_end_to_end():
     _say(compare(to_f64(out[0]), want, *tolerances("bf16"), what="searched layout"))
 
 
+def test_pattern_families_end_to_end():
+    """The three pattern families of Table 3 searched from GPU tile mass on structured heads (local,
+    cross, global): the library finds what the oracle's search finds on the oracle's mass, the
+    narrower families never return a second window, and the layout built from each answer runs
+    through the sparse kernel within tolerance."""
+    from oracle import search as OS
+    _say("pattern families")
+    T, H, W, tile, D = 6, 32, 32, (2, 8, 8), 128
+    gains = [(2.5, 2.5, 2.5), (1.0, 3.0, 3.0), (0.0, 0.0, 0.0)]
+    wl = make_workload("patterns", T, H, W, tile, 0, len(gains), D, "bf16", [[]] * len(gains))
+    g = geometry_of(wl)
+    probe = build_layout(ca, wl)
+    q, k, v = make_qkv(wl, DEV, axis_gain=gains)
+    mass = ca.compact_attn_tile_mass(ca.compact_attn_permute(q, probe), ca.compact_attn_permute(k, probe), probe)
+    torch.cuda.synchronize()
+    mass = mass[0].cpu().numpy()
+    want_mass = [OS.tile_mass(g, to_f64(q[0, h]), to_f64(k[0, h])) for h in range(len(gains))]
+    dts, tau, lam = [0, 1, 2], 0.9, 0.6
+    sparsity = {}
+    for pattern in ("cubic", "frame_groups", "dual"):
+        heads = []
+        for h in range(len(gains)):
+            groups, recall, kept = ca.compact_attn_search_head(probe, mass[h], dts, tau, lam, pattern)
+            want_groups, want_recall, want_kept = OS.search_head(g, want_mass[h], dts, tau, lam, pattern)
+            _say(pattern, "head", h, groups, "recall", round(recall, 4), "sparsity", round(1 - kept, 4))
+            assert groups == want_groups and abs(recall - want_recall) < 1e-4 and kept == pytest.approx(want_kept, abs=1e-12)
+            assert recall >= tau
+            if pattern != "dual":
+                assert all(b == ABSENT for _, _, b in groups)
+            heads.append(groups)
+            sparsity[pattern, h] = 1 - kept
+        found = make_workload("found", T, H, W, tile, 0, len(gains), D, "bf16", heads)
+        lay = build_layout(ca, found)
+        out, _ = gpu_attention(ca, found, lay, q, k, v)
+        torch.cuda.synchronize()
+        want = OA.masked_attention(g, heads, to_f64(q[0]), to_f64(k[0]), to_f64(v[0]))
+        _say(compare(to_f64(out[0]), want, *tolerances("bf16"), what=f"{pattern} layout"))
+    # the structure of Table 3 on these heads: the cross gains from the second window, the
+    # time-variant local head from per-group windows, the structureless head from nothing
+    assert sparsity["dual", 1] > sparsity["frame_groups", 1] + 0.1
+    assert sparsity["frame_groups", 0] > sparsity["cubic", 0] + 0.1
+    assert sparsity["dual", 2] == 0.0
+
+
 # ---------------------------------------------------------------- batch > 1
 
 @pytest.mark.parametrize("dtype,D,tile", [("bf16", 128, (2, 8, 8)), ("bf16", 64, (1, 8, 8)), ("f32", 64, (1, 4, 4))])

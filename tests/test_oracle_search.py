@@ -1,5 +1,6 @@
 """Pins for the oracle's tile mass and recall: closed forms and brute force."""
 import numpy as np
+import pytest
 
 from oracle.geometry import Geometry
 from oracle import attention as A
@@ -124,3 +125,54 @@ def test_reported_recall_equals_the_recall_of_the_built_mask():
         assert abs(mask.sum() / g.n ** 2 - kept) < 1e-12
         assert recall >= tau
         assert all(a[0] <= b[0] and a[1] >= b[1] for _, a, b in groups if b != ABSENT)   # wide / tall roles
+
+
+# ---------------------------------------------------------------- pattern families (the columns of Table 3)
+
+def test_pattern_families_closed_forms():
+    """A head whose exact support is known: a cross whose arms shrink with the frame distance.
+    dual finds the support itself; one window per group needs the bounding box of each group's
+    cross; a cube needs the bounding box of the widest group in every kept frame."""
+    g = _unit_tiles(4, 6, 8)
+    t, h, w = _coords(g)
+    dt, dh, dw = np.abs(t[:, None] - t), np.abs(h[:, None] - h), np.abs(w[:, None] - w)
+    near = (dt == 0) & (((dh == 0) & (dw <= 4)) | ((dw == 0) & (dh <= 3)))
+    mid = (dt == 1) & (((dh == 0) & (dw <= 2)) | ((dw == 0) & (dh <= 1)))
+    keep = near | mid
+    mass = keep / keep.sum(axis=1, keepdims=True)
+    bounds, tau, lam = [0, 1, 3], 1.0 - 1e-12, 0.5
+    dual, r2, k2 = S.search_head(g, mass, bounds, tau, lam, "dual")
+    assert dual == [(0, (0, 4), (3, 0)), (1, (0, 2), (1, 0)), (3, ABSENT, ABSENT)]
+    fg, r1, k1 = S.search_head(g, mass, bounds, tau, lam, "frame_groups")
+    assert fg == [(0, (3, 4), ABSENT), (1, (1, 2), ABSENT), (3, ABSENT, ABSENT)]
+    cube, r0, k0 = S.search_head(g, mass, bounds, tau, lam, "cubic")
+    assert cube == [(0, (3, 4), ABSENT), (1, (3, 4), ABSENT), (3, ABSENT, ABSENT)]
+    assert abs(r0 - 1) < 1e-12 and abs(r1 - 1) < 1e-12 and abs(r2 - 1) < 1e-12
+    assert k2 < k1 < k0 < 1.0                                            # each family strictly sparser here
+    for groups, kept in ((dual, k2), (fg, k1), (cube, k0)):
+        assert L.keep_mask_bruteforce(g, [groups])[0].sum() / g.n ** 2 == kept
+    assert k2 == keep.sum() / g.n ** 2
+
+
+def test_pattern_families_on_random_mass_report_their_own_mask():
+    g = Geometry(5, 9, 7, 1, 2, 2, 0)
+    rng = np.random.default_rng(6)
+    q, k = rng.standard_normal((2, g.N_real, 8))
+    q *= 3.0
+    k += 0.8 * np.repeat(rng.standard_normal((g.N_real // 7 + 1, 8)), 7, axis=0)[:g.N_real]
+    mass = S.tile_mass(g, q, k)
+    for pattern in S.PATTERNS:
+        for tau, lam in ((0.9, 0.5), (0.6, 1.5)):
+            groups, recall, kept = S.search_head(g, mass, [0, 1, 2, 4], tau, lam, pattern)
+            mask = L.keep_mask_bruteforce(g, [groups])[0]
+            assert abs(S.mask_recall(mass, mask) - recall) < 1e-12 and abs(mask.sum() / g.n ** 2 - kept) < 1e-12
+            assert recall >= tau
+            if pattern != "dual":
+                assert all(b == ABSENT for _, _, b in groups)
+            if pattern == "cubic":
+                live = [a for _, a, _ in groups if a != ABSENT]
+                assert len(set(live)) <= 1                                # one window
+                flags = [a != ABSENT for _, a, _ in groups]
+                assert flags == sorted(flags, reverse=True)               # kept groups are the innermost ones
+    with pytest.raises(ValueError):
+        S.search_head(g, mass, [0], 0.9, 0.5, "spiral")

@@ -7,6 +7,12 @@ Text tokens have pos = 0.  Q, K, V = 0.5 pos + N(0, 1) noise from three
 independent streams (seed, seed+1, seed+2), then rounded to the working
 dtype.  Tensors are natural order [batch, heads, N_real, D].
 
+`axis_gain` (optional, one (gt, gy, gx) triple per head) multiplies the positional code of Q and
+K on the channels of each axis: it shapes how fast a head's attention falls off along time, height
+and width (large on all axes: a local head; large on y and x with a small offset-free background:
+the arms of a cross; zero: a global head with no structure), standing in for the head kinds of
+Sec. 3.2.  V keeps the plain code.
+
 Values are drawn with torch on whichever device is asked for; the two sides
 of a parity test always read the same rounded tensor, so nothing depends on
 the generator being reproducible across devices.
@@ -34,10 +40,11 @@ def position_code(T, H, W, n_text, head_dim, device="cpu"):
     return pos
 
 
-def make_qkv(wl, device="cpu", q_gain=1.0):
+def make_qkv(wl, device="cpu", q_gain=1.0, axis_gain=None):
     """(q, k, v) natural order [batch, heads, N_real, D] in the workload's dtype."""
     dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[wl.dtype]
     pos = 0.5 * position_code(wl.T, wl.H, wl.W, wl.n_text, wl.head_dim, device)
+    channel_axis = torch.arange(wl.head_dim, device=device) % 3
     n_real = pos.shape[0]
     out = []
     for stream in range(3):
@@ -47,7 +54,11 @@ def make_qkv(wl, device="cpu", q_gain=1.0):
         for b in range(wl.batch):
             for h in range(wl.num_heads):
                 noise = torch.randn(n_real, wl.head_dim, generator=gen, device=device, dtype=torch.float32)
-                val = pos + noise
+                if axis_gain is not None and stream < 2:
+                    gain = torch.tensor([float(x) for x in axis_gain[h]], device=device, dtype=torch.float32)
+                    val = pos * gain[channel_axis][None, :] + noise
+                else:
+                    val = pos + noise
                 if stream == 0 and q_gain != 1.0:
                     val = val * q_gain
                 x[b, h] = val.to(dtype)
