@@ -141,9 +141,14 @@ int compact_attn_layout_order(const ca_layout* layout, const int32_t** order);
  * two tiles of pair i (same head, neighbours along one grid axis chosen per head so that the unions
  * are smallest; text tiles pair in id order), the second -1 when a tile has no partner.  Every row
  * of the layout is in exactly one pair.  Pairs are in launch order: descending union size, ties in
- * the order (head, first tile id).  *num_pairs is 0 for layouts the paired kernel does not serve.
+ * the order (head, first tile id).
+ *   *walk_ptr -> int64[*num_pairs + 1] offsets into *walk;  *walk -> int32 words, for pair i the
+ *   union of its two rows in ascending key-tile order, each word = tile id (bits 0-23)
+ *   | 1 << 30 if the first tile's row keeps it | 1 << 31 if the second tile's row keeps it.
+ * walk_ptr and walk may be NULL.  *num_pairs is 0 for layouts the paired kernel does not serve.
  * Owned by the layout, valid until it is freed. */
-int compact_attn_layout_pairs(const ca_layout* layout, const int32_t** pairs, int64_t* num_pairs);
+int compact_attn_layout_pairs(const ca_layout* layout, const int32_t** pairs, int64_t* num_pairs,
+                              const int64_t** walk_ptr, const int32_t** walk);
 
 /* Copy the layout's device-side tables (CSR, order, padding masks) to the current HIP device.
  * Synchronous; idempotent.  The compute calls below do it on first use if it was not called.

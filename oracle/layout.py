@@ -262,3 +262,22 @@ def pair_table(geom: Geometry, masks):
             entries.append((walked(masks[hd], (a, b)), hd * n + a, -1 if b < 0 else hd * n + b))
     order = sorted(range(len(entries)), key=lambda i: -entries[i][0])  # sorted() is stable
     return np.array([[entries[i][1], entries[i][2]] for i in order], dtype=np.int32).reshape(-1, 2)
+
+
+def pair_walks(masks, pairs):
+    """For every pair of `pair_table`: the key tiles either of its rows keeps, ascending, with who
+    keeps them.  Returns (walk_ptr int64[num_pairs + 1], tiles int32, in_first bool, in_second bool)."""
+    masks = np.asarray(masks, dtype=bool)
+    n = masks.shape[1]
+    flat = masks.reshape(-1, n)
+    ptr, tiles, first, second = [0], [], [], []
+    for a, b in np.asarray(pairs):
+        ra = flat[a]
+        rb = flat[b] if b >= 0 else np.zeros(n, dtype=bool)
+        ids = np.nonzero(ra | rb)[0]
+        tiles.append(ids)
+        first.append(ra[ids])
+        second.append(rb[ids])
+        ptr.append(ptr[-1] + len(ids))
+    cat = lambda parts, dt: np.concatenate(parts).astype(dt) if parts else np.zeros(0, dtype=dt)
+    return np.asarray(ptr, dtype=np.int64), cat(tiles, np.int32), cat(first, bool), cat(second, bool)

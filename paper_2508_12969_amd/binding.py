@@ -98,7 +98,8 @@ def load_library():
     lib.compact_attn_layout_info.argtypes = [vp, i64p, i64p, i64p, i64p, i64p]
     lib.compact_attn_layout_csr.argtypes = [vp, i32, ctypes.POINTER(i64p), ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
     lib.compact_attn_layout_order.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
-    lib.compact_attn_layout_pairs.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)), i64p]
+    lib.compact_attn_layout_pairs.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)), i64p, ctypes.POINTER(i64p),
+                                              ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
     lib.compact_attn_layout_upload.argtypes = [vp]
     lib.compact_attn_free_layout.argtypes = [vp]
     lib.compact_attn_free_layout.restype = None
@@ -226,13 +227,22 @@ def compact_attn_layout_order(layout):
 
 
 def compact_attn_layout_pairs(layout):
-    """int32 [num_pairs, 2] of row ids (second -1 for a single), in launch order; empty if unused."""
+    """(pairs int32 [num_pairs, 2] of row ids, second -1 for a single, in launch order;
+    walk_ptr int64 [num_pairs + 1]; walk int32 words: tile id | 1 << 30 (first keeps it) | 1 << 31 (second)).
+    All empty if the layout is not served by the paired kernel."""
     p = ctypes.POINTER(ctypes.c_int32)()
+    wp = ctypes.POINTER(ctypes.c_int64)()
+    w = ctypes.POINTER(ctypes.c_int32)()
     count = ctypes.c_int64(0)
-    _check(load_library().compact_attn_layout_pairs(layout.handle, ctypes.byref(p), ctypes.byref(count)))
+    _check(load_library().compact_attn_layout_pairs(layout.handle, ctypes.byref(p), ctypes.byref(count), ctypes.byref(wp),
+                                                    ctypes.byref(w)))
     if count.value == 0:
-        return np.zeros((0, 2), dtype=np.int32)
-    return np.ctypeslib.as_array(p, shape=(count.value, 2)).copy()
+        return np.zeros((0, 2), dtype=np.int32), np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32)
+    pairs = np.ctypeslib.as_array(p, shape=(count.value, 2)).copy()
+    walk_ptr = np.ctypeslib.as_array(wp, shape=(count.value + 1,)).copy()
+    total = int(walk_ptr[-1])
+    walk = np.ctypeslib.as_array(w, shape=(total,)).copy() if total else np.zeros(0, dtype=np.int32)
+    return pairs, walk_ptr, walk
 
 
 def compact_attn_layout_upload(layout):

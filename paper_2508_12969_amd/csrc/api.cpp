@@ -52,6 +52,9 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.dense_meta) (void)hipFree(d.dense_meta);
   if (d.order) (void)hipFree(d.order);
   if (d.pair_rows) (void)hipFree(d.pair_rows);
+  if (d.pair_walk_ptr) (void)hipFree(d.pair_walk_ptr);
+  if (d.pair_walk) (void)hipFree(d.pair_walk);
+  if (d.dense_pair_walk) (void)hipFree(d.dense_pair_walk);
   if (d.tile_class) (void)hipFree(d.tile_class);
   if (d.class_mask) (void)hipFree(d.class_mask);
   d = ca::DeviceTables{};
@@ -76,7 +79,7 @@ int ensure_uploaded(ca_layout* L) {
               L->class_mask.size());
     return CA_ERR_UNSUPPORTED;
   }
-  std::vector<int32_t> col_meta, dense_meta;
+  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk;
   try {
     std::vector<uint32_t> class_word(L->class_mask.size());
     const int words = (int)((L->B + 31) / 32);
@@ -90,6 +93,21 @@ int ensure_uploaded(ca_layout* L) {
       col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
     dense_meta.resize(L->n);
     for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)((uint32_t)t | class_word[L->tile_class[t]]);
+    if (!L->pair_rows.empty()) {
+      // walk words of the paired kernel carry the class in bits 24-29, below the two membership bits
+      if (L->class_mask.size() > 63) {
+        set_error("layout has too many padding classes for the paired kernel (%zu)", L->class_mask.size());
+        return CA_ERR_UNSUPPORTED;
+      }
+      pair_walk.assign(L->pair_walk.size() + 2, 0);
+      for (size_t i = 0; i < L->pair_walk.size(); ++i) {
+        const uint32_t w = (uint32_t)L->pair_walk[i];
+        pair_walk[i] = (int32_t)(w | ((uint32_t)L->tile_class[w & 0xffffffu] << 24));
+      }
+      dense_pair_walk.assign(L->n + 2, 0);
+      for (int64_t t = 0; t < L->n; ++t)
+        dense_pair_walk[t] = (int32_t)((uint32_t)t | ((uint32_t)L->tile_class[t] << 24) | ca::kPairInFirst | ca::kPairInSecond);
+    }
   } catch (const std::bad_alloc&) {
     set_error("out of host memory while packing the device tables");
     return CA_ERR_ALLOC;
@@ -101,6 +119,9 @@ int ensure_uploaded(ca_layout* L) {
   if (st == CA_OK) st = upload_vec(L->order.data(), L->order.size(), &d.order);
   if (st == CA_OK) st = upload_vec(L->pair_rows.data(), L->pair_rows.size(), &d.pair_rows);
   d.num_pairs = (int64_t)L->pair_rows.size() / 2;
+  if (st == CA_OK && d.num_pairs) st = upload_vec(L->pair_walk_ptr.data(), L->pair_walk_ptr.size(), &d.pair_walk_ptr);
+  if (st == CA_OK && d.num_pairs) st = upload_vec(pair_walk.data(), pair_walk.size(), &d.pair_walk);
+  if (st == CA_OK && d.num_pairs) st = upload_vec(dense_pair_walk.data(), dense_pair_walk.size(), &d.dense_pair_walk);
   if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
   if (st != CA_OK) {
@@ -153,6 +174,8 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   a.order = dense ? nullptr : L->dev.order;
   a.pair_rows = L->dev.pair_rows;
   a.num_pairs = L->dev.num_pairs;
+  a.pair_walk_ptr = dense ? nullptr : L->dev.pair_walk_ptr;
+  a.pair_walk = dense ? L->dev.dense_pair_walk : L->dev.pair_walk;
   a.tile_class = L->dev.tile_class;
   a.class_mask = L->dev.class_mask;
   a.batch = L->prob.batch;
@@ -299,11 +322,14 @@ int compact_attn_layout_order(const ca_layout* L, const int32_t** order) {
   return CA_OK;
 }
 
-int compact_attn_layout_pairs(const ca_layout* L, const int32_t** pairs, int64_t* num_pairs) {
+int compact_attn_layout_pairs(const ca_layout* L, const int32_t** pairs, int64_t* num_pairs, const int64_t** walk_ptr,
+                              const int32_t** walk) {
   ca::clear_error();
   if (!L || !pairs || !num_pairs) return fail(CA_ERR_INVALID_ARG, "null argument");
   *pairs = L->pair_rows.data();
   *num_pairs = (int64_t)L->pair_rows.size() / 2;
+  if (walk_ptr) *walk_ptr = L->pair_walk_ptr.data();
+  if (walk) *walk = L->pair_walk.data();
   return CA_OK;
 }
 

@@ -6,10 +6,12 @@
 // Here a workgroup owns the two neighbouring query tiles 2p and 2p+1 of one head: waves 0-1 work
 // for the first, waves 2-3 for the second, and both share one K and one V buffer.  The kept lists
 // of neighbours overlap almost completely (shifted windows, shared arms of a cross, every tile of
-// a global head), so the workgroup walks the merged list — a scalar two-pointer merge of the two
-// ascending CSR rows done on the fly — and copies each key tile once for both.  A wave sits out
-// the products of a tile its own query tile does not keep (wave-uniform branch) but takes part
-// in the copies and barriers.  Everything inside a tile step is as in attn_bf16.hip.
+// a global head), so the workgroup walks the union of the two lists, merged on the host into one
+// list of words (tile id, padding class, one membership bit per query tile), and copies each key
+// tile once for both.  A wave sits out the products of a tile its own query tile does not keep
+// (wave-uniform branch) but takes part in the copies and barriers.  The walk words are fetched two
+// steps ahead of their use, so that the scalar loads never stand between two steps.  Everything
+// inside a tile step is as in attn_bf16.hip.
 #include "attn_bf16_common.h"
 
 namespace ca {
@@ -24,7 +26,6 @@ struct PairShape {  // B = 64, D = 128, four waves
   static constexpr int kLoadsPerThread = kTileBytes / (kThreads * 16);  // 4
   static constexpr int kRowsPerLoad = 4;
 };
-constexpr int kNoTile = 0x1000000;  // larger than any tile id (ids use 24 bits)
 
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_pair_kernel(AttnArgs a) {
@@ -62,13 +63,11 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const char* Kp = static_cast<const char*>(a.k) + plane;
   const char* Vp = static_cast<const char*>(a.v) + plane;
 
-  // the two ascending lists of packed tile words (tile id | padding class << 24 | half-empty flag << 31)
-  const int64_t begin_a = a.row_ptr ? a.row_ptr[row_a] : 0;
-  const int count_a = (int)(a.row_ptr ? a.row_ptr[row_a + 1] - begin_a : a.n);
-  const int64_t begin_b = (a.row_ptr && has_b) ? a.row_ptr[row_b] : 0;
-  const int count_b = has_b ? (int)(a.row_ptr ? a.row_ptr[row_b + 1] - begin_b : a.n) : 0;
-  const auto list_a = CONST_PTR(int32_t, a.col_meta + begin_a);
-  const auto list_b = CONST_PTR(int32_t, a.col_meta + begin_b);
+  // the pair's walk: one word per tile of the union of the two rows, ascending tile ids:
+  // tile id | padding class << 24 | bit 30: kept by the first query tile | bit 31: by the second
+  const int64_t begin = a.pair_walk_ptr ? a.pair_walk_ptr[item] : 0;
+  const int count = (int)(a.pair_walk_ptr ? a.pair_walk_ptr[item + 1] - begin : a.n);
+  const auto walk = CONST_PTR(int32_t, a.pair_walk + begin);
   const auto tile_class = CONST_PTR(int32_t, a.tile_class);
   const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
 
@@ -113,37 +112,19 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_v;
   const float lazy_raw = kLazyLog2 / c2;
 
-  // ---- merged walk: scalar two-pointer merge, one step of look-ahead for the copies ----------
-  // heads of the two lists: packed word and tile id (kNoTile once a list is used up)
-  int ia = 0, ib = 0;
-  int32_t word_a = count_a > 0 ? list_a[0] : 0, word_b = count_b > 0 ? list_b[0] : 0;
-  int id_a = count_a > 0 ? (word_a & 0xffffff) : kNoTile, id_b = count_b > 0 ? (word_b & 0xffffff) : kNoTile;
-  int tile = min(id_a, id_b);
-  bool use_a = id_a == tile, use_b = id_b == tile;  // meaningless when tile == kNoTile, never read then
-  int32_t word = use_a ? word_a : word_b;
-  if (tile != kNoTile) {
-    k_loader.issue(Kp + (int64_t)tile * S::kTileBytes, lds_k_addr, wave);
-    v_loader.issue(Vp + (int64_t)tile * S::kTileBytes, lds_v_addr, wave);
+  // ---- the walk, with its words two steps ahead (the table is readable two words past its end) --
+  int32_t word = walk[0], word1 = walk[1];
+  if (count > 0) {
+    k_loader.issue(Kp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_k_addr, wave);
+    v_loader.issue(Vp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_v_addr, wave);
   }
 
-  while (tile != kNoTile) {
-    // advance the lists past the current tile and look at the next merged entry
-    if (use_a) {
-      ++ia;
-      word_a = ia < count_a ? list_a[ia] : 0;
-      id_a = ia < count_a ? (word_a & 0xffffff) : kNoTile;
-    }
-    if (use_b) {
-      ++ib;
-      word_b = ib < count_b ? list_b[ib] : 0;
-      id_b = ib < count_b ? (word_b & 0xffffff) : kNoTile;
-    }
-    const int next_tile = min(id_a, id_b);
-    const bool next_a = id_a == next_tile, next_b = id_b == next_tile;
-    const int32_t next_word = next_a ? word_a : word_b;
-    const bool more = next_tile != kNoTile;
-    const bool mine = wave_active && (member ? use_b : use_a);
-    const int cls = (word >> 24) & 0x7f;
+  for (int j = 0; j < count; ++j) {
+    const int32_t word2 = walk[j + 2];
+    const int next_tile = word1 & 0xffffff;
+    const bool more = j + 1 < count;
+    const bool mine = wave_active && ((word >> (30 + member)) & 1);
+    const int cls = (word >> 24) & 0x3f;
 
     // ---- S^T = K Q^T ----------------------------------------------------------------------
     WAIT_VMCNT(S::kLoadsPerThread);  // K landed (V may still be in flight)
@@ -252,10 +233,8 @@ void attn_bf16_pair_kernel(AttnArgs a) {
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V
     if (more) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
-    tile = next_tile;
-    use_a = next_a;
-    use_b = next_b;
-    word = next_word;
+    word = word1;
+    word1 = word2;
   }
 
   // ---- epilogue: O = O^T / l, padding queries and empty rows give zeros ------------------------

@@ -31,6 +31,9 @@ struct AttnArgs {
   const int32_t* order;        // device; null = identity
   const int32_t* pair_rows;    // device [2*num_pairs]; row ids of the two query tiles of a workgroup (-1: none), paired kernel only
   int64_t num_pairs;
+  const int64_t* pair_walk_ptr; // device [num_pairs + 1]; null selects the dense walk: every pair uses pair_walk[0..n)
+  const int32_t* pair_walk;     // device; per walked tile: tile id | padding class << 24 | kPairInFirst | kPairInSecond,
+                                // readable two words past the last entry
   const int32_t* tile_class;   // device [n]
   const SlotMask* class_mask;  // device
   int32_t batch, num_heads;

@@ -7,6 +7,7 @@
 // walks frames and tile rows in ascending order and emits those intervals, which yields the
 // ascending tile ids directly.  No HIP call is made here.
 #include <algorithm>
+#include <cstdint>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -220,6 +221,24 @@ static void build_pair_table(ca_layout& L) {
   std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& x, const Pair& y) { return x.walked > y.walked; });
   pair_rows.resize(2 * pairs.size());
   for (size_t i = 0; i < pairs.size(); ++i) pair_rows[2 * i] = pairs[i].a, pair_rows[2 * i + 1] = pairs[i].b;
+  // The walk of a pair: the union of its two rows in ascending tile order, one word per tile:
+  // tile id | kPairInFirst if the first row keeps the tile | kPairInSecond if the second does.
+  L.pair_walk_ptr.assign(pairs.size() + 1, 0);
+  for (size_t i = 0; i < pairs.size(); ++i) L.pair_walk_ptr[i + 1] = L.pair_walk_ptr[i] + pairs[i].walked;
+  L.pair_walk.resize((size_t)L.pair_walk_ptr[pairs.size()]);
+  for (size_t p = 0; p < pairs.size(); ++p) {
+    const int64_t ra = pairs[p].a, rb = pairs[p].b;
+    int64_t i = L.row_ptr[ra], ie = L.row_ptr[ra + 1];
+    int64_t j = rb < 0 ? 0 : L.row_ptr[rb], je = rb < 0 ? 0 : L.row_ptr[rb + 1];
+    int64_t o = L.pair_walk_ptr[p];
+    while (i < ie || j < je) {
+      const int32_t ti = i < ie ? L.col_idx[i] : INT32_MAX, tj = j < je ? L.col_idx[j] : INT32_MAX;
+      const int32_t t = ti < tj ? ti : tj;
+      L.pair_walk[o++] = (int32_t)((uint32_t)t | (ti == t ? kPairInFirst : 0u) | (tj == t ? kPairInSecond : 0u));
+      i += ti == t;
+      j += tj == t;
+    }
+  }
 }
 
 void finish_host_tables(ca_layout& L) {
@@ -234,6 +253,8 @@ void finish_host_tables(ca_layout& L) {
   build_order(L);
   build_slot_masks(L);
   L.pair_rows.clear();
+  L.pair_walk_ptr.clear();
+  L.pair_walk.clear();
   if (L.prob.dtype == CA_BF16 && L.B == 64 && L.prob.head_dim == 128) build_pair_table(L);
 }
 

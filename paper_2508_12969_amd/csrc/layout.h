@@ -10,6 +10,9 @@
 
 namespace ca {
 
+// Membership bits of a walk word of the paired kernel (bits 30 and 31; the tile id is below bit 24).
+constexpr uint32_t kPairInFirst = 1u << 30, kPairInSecond = 1u << 31;
+
 // Validity of the B token slots of a tile, one bit per slot (B <= 128).
 struct SlotMask {
   uint32_t w[4];
@@ -23,6 +26,9 @@ struct DeviceTables {
   int32_t* order = nullptr;      // [num_heads*n] launch order of row ids head*n + tile
   int32_t* pair_rows = nullptr;  // [2*num_pairs] row ids of the two query tiles a workgroup of the paired kernel owns (-1: none), in launch order
   int64_t num_pairs = 0;
+  int64_t* pair_walk_ptr = nullptr;   // [num_pairs + 1]
+  int32_t* pair_walk = nullptr;       // packed walk words (tile id | class << 24 | membership bits), two words of padding
+  int32_t* dense_pair_walk = nullptr; // [n + 2] the walk 0..n-1 kept by both tiles (dense path)
   int32_t* tile_class = nullptr; // [n] index into class_mask; 0 = every slot holds a token
   SlotMask* class_mask = nullptr; // [num_classes]
 };
@@ -41,6 +47,8 @@ struct ca_layout {
   std::vector<std::vector<int64_t>> head_row_ptr;  // per head, relative offsets (C-ABI view)
   std::vector<int32_t> order;               // [num_heads*n]
   std::vector<int32_t> pair_rows;           // [2*num_pairs], empty unless the paired kernel serves this layout
+  std::vector<int64_t> pair_walk_ptr;       // [num_pairs + 1] offsets into pair_walk
+  std::vector<int32_t> pair_walk;           // per pair: union of its two rows, tile id | kPairInFirst | kPairInSecond
   std::vector<int32_t> tile_class;          // [n]
   std::vector<ca::SlotMask> class_mask;     // class 0 = all valid
 

@@ -326,8 +326,20 @@ def test_pair_table_bit_exact(case):
     g = Geometry(T, H, W, *tile, n_text)
     lay = ca.compact_attn_build_layout(T, H, W, tile, n_text, 1, len(heads), 128, "bf16", heads)
     masks = np.stack([OL.mask_of_csr(g.n, *csr) for csr in OL.build_csr(g, heads)])
-    assert np.array_equal(ca.compact_attn_layout_pairs(lay), OL.pair_table(g, masks))
+    _check_pairs(lay, g, masks)
     lay.free()
+
+
+def _check_pairs(lay, g, masks):
+    pairs, walk_ptr, walk = ca.compact_attn_layout_pairs(lay)
+    want = OL.pair_table(g, masks)
+    assert np.array_equal(pairs, want)
+    want_ptr, tiles, first, second = OL.pair_walks(masks, want)
+    assert np.array_equal(walk_ptr, want_ptr)
+    words = walk.view(np.uint32)
+    assert np.array_equal(words & 0xFFFFFF, tiles)
+    assert np.array_equal((words >> 30) & 1, first) and np.array_equal(words >> 31, second)
+    assert not np.any(words & 0x3F000000)
 
 
 def test_pair_table_of_config3_heads_and_absent_elsewhere():
@@ -337,10 +349,10 @@ def test_pair_table_of_config3_heads_and_absent_elsewhere():
     heads = [wl.heads[h] for h in picked]
     lay = ca.compact_attn_build_layout(wl.T, wl.H, wl.W, wl.tile, wl.n_text, 1, len(heads), wl.head_dim, wl.dtype, heads)
     masks = np.stack([OL.mask_of_csr(g.n, *csr) for csr in OL.build_csr(g, heads)])
-    assert np.array_equal(ca.compact_attn_layout_pairs(lay), OL.pair_table(g, masks))
+    _check_pairs(lay, g, masks)
     lay.free()
     # layouts served by the one-tile-per-workgroup kernels carry no pair table
     for name in ("cfg1", "cfg2"):
         lay = build_layout(ca, get_workload(name))
-        assert ca.compact_attn_layout_pairs(lay).shape == (0, 2)
+        assert ca.compact_attn_layout_pairs(lay)[0].shape == (0, 2)
         lay.free()

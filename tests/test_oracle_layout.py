@@ -212,6 +212,11 @@ def test_pair_table_hand_worked():
     g = Geometry(1, 8, 24, 1, 8, 8, 192)
     masks = L.keep_mask_bruteforce(g, [[(0, (0, 0), (-1, -1))]])
     assert L.pair_table(g, masks).tolist() == [[3, 4], [5, -1], [0, 1], [2, -1]]
+    ptr, tiles, first, second = L.pair_walks(masks, L.pair_table(g, masks))
+    assert ptr.tolist() == [0, 6, 12, 17, 21]
+    assert tiles[12:17].tolist() == [0, 1, 3, 4, 5] and first[12:17].tolist() == [True, False, True, True, True]
+    assert second[12:17].tolist() == [False, True, True, True, True]
+    assert tiles[17:].tolist() == [2, 3, 4, 5] and first[17:].all() and not second[17:].any()
     # a single tile: nothing to pair with
     g = Geometry(1, 8, 8, 1, 8, 8, 0)
     assert L.pair_table(g, np.ones((1, 1, 1), bool)).tolist() == [[0, -1]]
