@@ -88,10 +88,11 @@ int ensure_uploaded(ca_layout* L) {
       for (int w = words / 2; w < words; ++w) upper_empty = upper_empty && L->class_mask[c].w[w] == 0;
       class_word[c] = ((uint32_t)c << 24) | (upper_empty ? 0x80000000u : 0u);
     }
-    col_meta.resize(L->col_idx.size());
-    for (size_t i = 0; i < col_meta.size(); ++i)
+    // two words of padding: the kernels fetch these tables two entries ahead of the one in use
+    col_meta.assign(L->col_idx.size() + 2, 0);
+    for (size_t i = 0; i < L->col_idx.size(); ++i)
       col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
-    dense_meta.resize(L->n);
+    dense_meta.assign(L->n + 2, 0);
     for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)((uint32_t)t | class_word[L->tile_class[t]]);
     if (!L->pair_rows.empty()) {
       // walk words of the paired kernel carry the class in bits 24-29, below the two membership bits

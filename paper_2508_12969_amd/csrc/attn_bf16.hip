@@ -129,9 +129,12 @@ void attn_bf16_kernel(AttnArgs a) {
   const uint32_t lds_v_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_v;
 
   const float lazy_raw = kLazyLog2 / c2;  // kLazyLog2 in raw score units
-  int32_t word = 0;
+  // the packed words are fetched two steps ahead of their use (the tables are readable two words
+  // past their end), so that no scalar load is waited for between two steps
+  int32_t word = 0, word1 = 0;
   if (count > 0) {
     word = meta[0];
+    word1 = meta[1];
     k_loader.issue(Kp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_k_addr, wave);
     v_loader.issue(Vp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_v_addr, wave);
   }
@@ -152,8 +155,8 @@ void attn_bf16_kernel(AttnArgs a) {
   }
 
   for (int j = 0; j < active_count; ++j) {
-    const int32_t next_word = (j + 1 < count) ? meta[j + 1] : 0;
-    const int next_tile = next_word & 0xffffff;
+    const int32_t word2 = meta[j + 2];
+    const int next_tile = word1 & 0xffffff;
     const int cls = (word >> 24) & 0x7f;
     // keys B/2 .. B-1 of this tile are padding only: the products of the upper key blocks are skipped
     const bool upper_keys = word >= 0;
@@ -317,7 +320,8 @@ void attn_bf16_kernel(AttnArgs a) {
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V(j)
     if (j + 1 < count) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
-    word = next_word;
+    word = word1;
+    word1 = word2;
   }
 
   // ---- epilogue: O = O^T / l, padding queries and empty rows give zeros ------------------------

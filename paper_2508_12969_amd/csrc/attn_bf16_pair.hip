@@ -42,13 +42,14 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const int g = lane >> 5;       // lane group: which half of every 8-key / 8-d pair this lane holds
 
   const int64_t pairs = a.num_pairs;
-  // XCD-aware launch order: see attn_bf16.hip
+  // XCD-aware launch order as in attn_bf16.hip; an XCD holds 64 of these workgroups at a time
+  constexpr int kChunk = 64;
   int64_t linear = blockIdx.x;
   {
-    const int64_t span = 8 * (int64_t)kXcdChunk, total = pairs * a.batch;
+    const int64_t span = 8 * (int64_t)kChunk, total = pairs * a.batch;
     if (linear < total / span * span) {
       const int64_t xcd = linear & 7, seq = linear >> 3;
-      linear = (seq / kXcdChunk) * span + xcd * kXcdChunk + seq % kXcdChunk;
+      linear = (seq / kChunk) * span + xcd * kChunk + seq % kChunk;
     }
   }
   const int64_t item = linear % pairs;

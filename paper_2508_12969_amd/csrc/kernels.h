@@ -27,7 +27,7 @@ struct AttnArgs {
   const void* v;
   void* out;
   const int64_t* row_ptr;      // device; null selects the dense walk: every row uses col_meta[0..n)
-  const int32_t* col_meta;     // device; per kept tile: tile id | padding class << 24
+  const int32_t* col_meta;     // device; per kept tile: tile id | padding class << 24; readable two words past the end
   const int32_t* order;        // device; null = identity
   const int32_t* pair_rows;    // device [2*num_pairs]; row ids of the two query tiles of a workgroup (-1: none), paired kernel only
   int64_t num_pairs;
