@@ -41,6 +41,9 @@ def parse():
                     help="also launch one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--mass-calls", type=int, default=2, help="timed calls of the tile-mass kernel (0 = skip)")
+    ap.add_argument("--natural-calls", type=int, default=3,
+                    help="timed calls of compact_attn_forward_natural, the forward with the gather / scatter fused in "
+                         "(0 = skip)")
     ap.add_argument("--pattern-report", action="store_true",
                     help="also search masks under the three pattern families of Table 3 on structured synthetic heads "
                          "and report the sparsity each family reaches")
@@ -252,6 +255,27 @@ def main():
                 "row_sum_error": float((m_out[0].sum(dim=2).sum(dim=1) - lay.n_tokens_real).abs().max())}
         del m_out
 
+    fused = None
+    if args.natural_calls > 0 and wl.dtype == "bf16":
+        # the same whole path in one launch: tiles gathered from natural order inside the kernel
+        try:
+            o2 = ca.compact_attn_forward_natural(q, k, v, lay)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(args.natural_calls):
+                a, b = ev(), ev()
+                a.record()
+                ca.compact_attn_forward_natural(q, k, v, lay, out=o2)
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            nat_ms = sorted(ts)[len(ts) // 2]
+            fused = {"ms_per_step": nat_ms, "tflops": flops / nat_ms / 1e9, "speedup_vs_permuted_path": ms_per_step / nat_ms,
+                     "same_bits_as_permuted_path": bool(torch.equal(o2, out))}
+            del o2
+        except ca.CompactAttnError as exc:
+            fused = {"unsupported": str(exc)}
+
     sweep = {}
     if args.sweep:
         for name in ("cfg4-S50", "cfg4-S65", "cfg4-S80"):
@@ -307,6 +331,7 @@ def main():
                      "algorithmic_flops_per_launch": flops,
                      "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * lay.n_tokens_padded * D * esz},
         "tile_mass": mass,
+        "fused_gather_scatter": fused,
         "cpu_baseline": cpu,
     }
     if sweep:

@@ -178,6 +178,17 @@ int compact_attn_permute(const void* src, void* dst, ca_layout* layout, int32_t 
 int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
                          void* stream);
 
+/* The same forward on tensors in NATURAL token order (Sec. 3.1's tile-wise flattening and its inverse
+ * folded into the attention pass: the kernel gathers the K/V tiles and the Q rows from natural
+ * order and scatters the output rows back, so no compact_attn_permute pass is needed).
+ *   q, k, v, out: device pointers, [batch, heads, N_real, D] in natural order; out must not alias
+ *   q/k/v.  Every row of out is written (zeros for a query whose kept set holds no real key).
+ * Same arithmetic per query as compact_attn_forward.  Supported: bf16 with (B, D) as for
+ * compact_attn_forward and a tile width tw that is a multiple of 1024 / (2*D) tokens (4 for D = 128,
+ * 8 for D = 64); otherwise CA_ERR_UNSUPPORTED. */
+int compact_attn_forward_natural(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
+                                 void* stream);
+
 /* Same kernel with every query tile keeping all n tiles (the full-attention starting point of
  * Sec. 4.2 and the baseline of Sec. 5.1); the per-head windows of the layout are ignored. */
 int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* layout, void* out,

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     compact_attn_build_layout,
     compact_attn_dense,
     compact_attn_forward,
+    compact_attn_forward_natural,
     compact_attn_free_layout,
     compact_attn_last_error,
     compact_attn_layout_csr,

@@ -35,6 +35,7 @@ EXPORTED = (
     "compact_attn_free_layout",
     "compact_attn_permute",
     "compact_attn_forward",
+    "compact_attn_forward_natural",
     "compact_attn_dense",
     "compact_attn_tile_mass",
     "compact_attn_search_head",
@@ -105,6 +106,7 @@ def load_library():
     lib.compact_attn_free_layout.restype = None
     lib.compact_attn_permute.argtypes = [vp, vp, vp, i32, vp]
     lib.compact_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.compact_attn_forward_natural.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_dense.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_tile_mass.argtypes = [vp, vp, vp, vp, vp]
     lib.compact_attn_search_head.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32, ctypes.c_double,
@@ -288,13 +290,13 @@ def compact_attn_permute(src, layout, inverse=False, out=None, stream=None):
     return out
 
 
-def _attention(fn, q, k, v, layout, out, stream):
+def _attention(fn, q, k, v, layout, out, stream, padded=True):
     import torch
     for name, t in (("q", q), ("k", k), ("v", v)):
-        _check_tensor(t, layout, True, name)
+        _check_tensor(t, layout, padded, name)
     if out is None:
         out = torch.empty_like(q)
-    _check_tensor(out, layout, True, "out")
+    _check_tensor(out, layout, padded, "out")
     _check(fn(ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
               layout.handle, ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)))
     return out
@@ -303,6 +305,11 @@ def _attention(fn, q, k, v, layout, out, stream):
 def compact_attn_forward(q, k, v, layout, out=None, stream=None):
     """Sparse attention over tile-ordered, padded q/k/v [batch, heads, N_pad, D]."""
     return _attention(load_library().compact_attn_forward, q, k, v, layout, out, stream)
+
+
+def compact_attn_forward_natural(q, k, v, layout, out=None, stream=None):
+    """Sparse attention over natural-order q/k/v [batch, heads, N_real, D]; the result is in natural order too."""
+    return _attention(load_library().compact_attn_forward_natural, q, k, v, layout, out, stream, padded=False)
 
 
 def compact_attn_tile_mass(q, k, layout, out=None, stream=None):

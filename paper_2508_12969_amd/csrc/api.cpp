@@ -57,6 +57,7 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.dense_pair_walk) (void)hipFree(d.dense_pair_walk);
   if (d.tile_class) (void)hipFree(d.tile_class);
   if (d.class_mask) (void)hipFree(d.class_mask);
+  if (d.tile_origin) (void)hipFree(d.tile_origin);
   d = ca::DeviceTables{};
 }
 
@@ -79,7 +80,7 @@ int ensure_uploaded(ca_layout* L) {
               L->class_mask.size());
     return CA_ERR_UNSUPPORTED;
   }
-  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk;
+  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk, tile_origin;
   try {
     std::vector<uint32_t> class_word(L->class_mask.size());
     const int words = (int)((L->B + 31) / 32);
@@ -94,6 +95,20 @@ int ensure_uploaded(ca_layout* L) {
       col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
     dense_meta.assign(L->n + 2, 0);
     for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)((uint32_t)t | class_word[L->tile_class[t]]);
+    // natural-order row of slot 0 of every tile (kernels that gather tiles from natural order)
+    const ca_problem& pr = L->prob;
+    const int64_t n_video = (int64_t)pr.T * pr.H * pr.W;
+    if (L->N_real < ((int64_t)1 << 31)) {
+      tile_origin.resize(L->n);
+      for (int64_t t = 0; t < L->n; ++t) {
+        if (t >= L->n_vid) {
+          tile_origin[t] = (int32_t)(n_video + (t - L->n_vid) * L->B);
+        } else {
+          const int64_t kw = t % L->nW, kh = (t / L->nW) % L->nH, kt = t / ((int64_t)L->nW * L->nH);
+          tile_origin[t] = (int32_t)(((kt * pr.tt) * pr.H + kh * pr.th) * pr.W + kw * pr.tw);
+        }
+      }
+    }
     if (!L->pair_rows.empty()) {
       // walk words of the paired kernel carry the class in bits 24-29, below the two membership bits
       if (L->class_mask.size() > 63) {
@@ -125,6 +140,7 @@ int ensure_uploaded(ca_layout* L) {
   if (st == CA_OK && d.num_pairs) st = upload_vec(dense_pair_walk.data(), dense_pair_walk.size(), &d.dense_pair_walk);
   if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
+  if (st == CA_OK && !tile_origin.empty()) st = upload_vec(tile_origin.data(), tile_origin.size(), &d.tile_origin);
   if (st != CA_OK) {
     free_device_tables(d);
     return st;
@@ -155,7 +171,8 @@ int check_attn_support(const ca_layout* L) {
   return CA_OK;
 }
 
-int run_attention(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream, bool dense) {
+int run_attention(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream, bool dense,
+                  bool natural = false) {
   ca::clear_error();
   if (!q || !k || !v || !L || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
@@ -163,6 +180,15 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   if (out == q || out == k || out == v) return fail(CA_ERR_INVALID_ARG, "out must not alias q, k or v");
   int st = check_attn_support(L);
   if (st != CA_OK) return st;
+  if (natural) {
+    const ca_problem& p = L->prob;
+    const int rows_per_block = 1024 / (p.head_dim * 2);
+    if (p.dtype != CA_BF16 || p.tw % rows_per_block != 0 || L->N_real >= ((int64_t)1 << 31)) {
+      set_error("natural-order attention needs bf16 and a tile width that is a multiple of %d tokens (head_dim %d); got tw=%d",
+                rows_per_block, p.head_dim, p.tw);
+      return CA_ERR_UNSUPPORTED;
+    }
+  }
   st = ensure_uploaded(L);
   if (st != CA_OK) return st;
   ca::AttnArgs a{};
@@ -185,6 +211,14 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   a.B = (int32_t)L->B;
   a.D = L->prob.head_dim;
   a.scale = L->scale;
+  a.natural = natural ? 1 : 0;
+  a.tile_origin = L->dev.tile_origin;
+  a.H = L->prob.H;
+  a.W = L->prob.W;
+  a.th = L->prob.th;
+  a.tw = L->prob.tw;
+  a.n_vid = L->n_vid;
+  a.N_real = L->N_real;
   const hipError_t e = L->prob.dtype == CA_BF16 ? ca::launch_attn_bf16(a, (hipStream_t)stream)
                                                 : ca::launch_attn_f32(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, dense ? "dense attention launch" : "sparse attention launch");
@@ -374,6 +408,10 @@ int compact_attn_permute(const void* src, void* dst, ca_layout* L, int32_t inver
 
 int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {
   return run_attention(q, k, v, L, out, stream, false);
+}
+
+int compact_attn_forward_natural(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {
+  return run_attention(q, k, v, L, out, stream, false, true);
 }
 
 int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {

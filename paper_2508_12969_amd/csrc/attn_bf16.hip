@@ -38,7 +38,10 @@
 namespace ca {
 namespace {
 
-template <int B, int D>
+// kNat: q, k, v and out are in natural token order ([batch, heads, N_real, D]); the gather of the
+// tiles and the scatter of the output happen in the copies of this kernel instead of in separate
+// permutation passes.
+template <int B, int D, bool kNat>
 __global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_kernel(AttnArgs a) {
   using S = Shape<B, D>;
@@ -67,9 +70,50 @@ void attn_bf16_kernel(AttnArgs a) {
   const int64_t batch = linear / rows;
   const int64_t row = a.order ? a.order[item] : item;
   const int64_t head = row / a.n, q_tile = row - head * a.n;
-  const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
+  const int64_t plane = (batch * a.num_heads + head) * (kNat ? a.N_real * (int64_t)S::kRowBytes : a.n * (int64_t)S::kTileBytes);
   const char* Kp = static_cast<const char*>(a.k) + plane;
   const char* Vp = static_cast<const char*>(a.v) + plane;
+  // Natural order: a KiB block of a tile (kRowsPerLoad consecutive slots, inside one run of tw
+  // tokens) is contiguous there too, at row tile_origin[tile] + (dt*H + dy)*W + dx of the plane; a
+  // text tile is contiguous as a whole.  row_in_tile[i] is that offset for the i-th block this wave copies.
+  const auto tile_origin = CONST_PTR(int32_t, a.tile_origin);
+  int32_t row_in_tile[kNat ? S::kLoadsPerThread : 1];
+  if constexpr (kNat) {
+#pragma unroll
+    for (int i = 0; i < S::kLoadsPerThread; ++i) {
+      const int slot0 = (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad;
+      const int dx = slot0 % a.tw, run = slot0 / a.tw, dy = run % a.th, dt = run / a.th;
+      row_in_tile[i] = (dt * a.H + dy) * a.W + dx;
+    }
+  }
+  // copy of one tile: tile order = one contiguous block; natural order = one base per KiB block
+  auto issue_tile = [&](const auto& loader, const char* base, int tile, int32_t origin, uint32_t lds_addr) {
+    if constexpr (!kNat) {
+      loader.issue(base + (int64_t)tile * S::kTileBytes, lds_addr, wave);
+    } else {
+      const bool text = tile >= a.n_vid;
+      const char* sb[S::kLoadsPerThread];
+      bool inside = true;
+#pragma unroll
+      for (int i = 0; i < S::kLoadsPerThread; ++i) {
+        const int32_t row = origin + (text ? (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad : row_in_tile[i]);
+        inside = inside && row + S::kRowsPerLoad <= a.N_real;
+        sb[i] = base + (int64_t)row * S::kRowBytes;
+      }
+      if (inside) {
+        loader.issue_blocks(sb, lds_addr, wave);
+      } else {
+        // slots past the last token (padding of the last tiles): every lane is pointed at a row of the
+        // tensor; what it fetches is never attended
+#pragma unroll
+        for (int i = 0; i < S::kLoadsPerThread; ++i) {
+          const int32_t row = origin + (text ? (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad : row_in_tile[i]);
+          const int32_t first = min(row, (int32_t)a.N_real - 1);
+          loader.issue_clamped(base + (int64_t)first * S::kRowBytes, (int32_t)a.N_real - 1 - first, i, lds_addr, wave, lane);
+        }
+      }
+    }
+  };
 
   const int64_t begin = a.row_ptr ? a.row_ptr[row] : 0;
   const int count = (int)(a.row_ptr ? a.row_ptr[row + 1] - begin : a.n);
@@ -86,7 +130,13 @@ void attn_bf16_kernel(AttnArgs a) {
   const bool wave_active = q_valid != 0;
 
   // Q fragment: B operand of S^T, lane (qi, g) holds d = 16*step + 8*g .. +7 of its query.
-  const int64_t q_row = q_tile * B + wave * 32 + qi;
+  int64_t q_row = q_tile * B + wave * 32 + qi;
+  if constexpr (kNat) {
+    const int slot = wave * 32 + qi;
+    const int dx = slot % a.tw, run = slot / a.tw, dy = run % a.th, dt = run / a.th;
+    const int64_t row = tile_origin[q_tile] + (q_tile >= a.n_vid ? slot : (dt * a.H + dy) * a.W + dx);
+    q_row = row < a.N_real ? row : a.N_real - 1;  // a padding slot reads some real row; its result is not stored
+  }
   bf16x8 qf[S::kQkSteps];
   {
     const char* Qp = static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes + g * 16;
@@ -135,28 +185,31 @@ void attn_bf16_kernel(AttnArgs a) {
   if (count > 0) {
     word = meta[0];
     word1 = meta[1];
-    k_loader.issue(Kp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_k_addr, wave);
-    v_loader.issue(Vp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_v_addr, wave);
+    const int32_t origin = kNat ? tile_origin[word & 0xffffff] : 0;
+    issue_tile(k_loader, Kp, word & 0xffffff, origin, lds_k_addr);
+    issue_tile(v_loader, Vp, word & 0xffffff, origin, lds_v_addr);
   }
 
   // A wave without real queries only moves tiles: the same copies, waits and barriers as below.
   const int active_count = wave_active ? count : 0;
   for (int j = active_count; j < count; ++j) {
     const int next_tile = (j + 1 < count) ? (meta[j + 1] & 0xffffff) : 0;
+    const int32_t next_origin = kNat ? tile_origin[next_tile] : 0;
     WAIT_VMCNT(S::kLoadsPerThread);
     BARRIER();
     BARRIER();
-    if (j + 1 < count) k_loader.issue(Kp + (int64_t)next_tile * S::kTileBytes, lds_k_addr, wave);
+    if (j + 1 < count) issue_tile(k_loader, Kp, next_tile, next_origin, lds_k_addr);
     if (j + 1 < count) WAIT_VMCNT(S::kLoadsPerThread);
     else WAIT_VMCNT(0);
     BARRIER();
     BARRIER();
-    if (j + 1 < count) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
+    if (j + 1 < count) issue_tile(v_loader, Vp, next_tile, next_origin, lds_v_addr);
   }
 
   for (int j = 0; j < active_count; ++j) {
     const int32_t word2 = meta[j + 2];
     const int next_tile = word1 & 0xffffff;
+    const int32_t next_origin = kNat ? tile_origin[next_tile] : 0;  // requested a phase ahead of the copy that uses it
     const int cls = (word >> 24) & 0x7f;
     // keys B/2 .. B-1 of this tile are padding only: the products of the upper key blocks are skipped
     const bool upper_keys = word >= 0;
@@ -195,7 +248,7 @@ void attn_bf16_kernel(AttnArgs a) {
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading K(j)
-    if (j + 1 < count) k_loader.issue(Kp + (int64_t)next_tile * S::kTileBytes, lds_k_addr, wave);
+    if (j + 1 < count) issue_tile(k_loader, Kp, next_tile, next_origin, lds_k_addr);
 
     bf16x8 pf[S::kKeyBlocks][2];
     {
@@ -319,7 +372,7 @@ void attn_bf16_kernel(AttnArgs a) {
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V(j)
-    if (j + 1 < count) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
+    if (j + 1 < count) issue_tile(v_loader, Vp, next_tile, next_origin, lds_v_addr);
     word = word1;
     word1 = word2;
   }
@@ -329,6 +382,7 @@ void attn_bf16_kernel(AttnArgs a) {
   const bool q_real = (q_valid >> qi) & 1u;
   const float inv = (q_real && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
   char* Op = static_cast<char*>(a.out) + plane + q_row * S::kRowBytes;
+  if (kNat && !q_real) return;  // natural order has no row for a padding slot
 #pragma unroll
   for (int db = 0; db < S::kDBlocks; ++db)
 #pragma unroll
@@ -344,7 +398,12 @@ void attn_bf16_kernel(AttnArgs a) {
 template <int B, int D>
 hipError_t launch(const AttnArgs& a, hipStream_t stream) {
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
-  hipLaunchKernelGGL((attn_bf16_kernel<B, D>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
+  if (a.natural) {
+    if (a.tw % Shape<B, D>::kRowsPerLoad != 0) return hipErrorInvalidValue;  // a KiB block must stay inside one run
+    hipLaunchKernelGGL((attn_bf16_kernel<B, D, true>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((attn_bf16_kernel<B, D, false>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
+  }
   return hipGetLastError();
 }
 
@@ -356,7 +415,8 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
   if (items > 0x7fffffff) return hipErrorInvalidValue;
   if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
   if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
-  if (a.B == 64 && a.D == 128) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
+  if (a.B == 64 && a.D == 128 && !a.natural) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
+  if (a.B == 64 && a.D == 128) return launch<64, 128>(a, stream);
   if (a.B == 64 && a.D == 64) return launch<64, 64>(a, stream);
   return hipErrorInvalidValue;
 }

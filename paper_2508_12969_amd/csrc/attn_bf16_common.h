@@ -98,6 +98,42 @@ struct TileLoader {
           : "memory");
     }
   }
+
+  // The same copy with one global base per KiB block (a tile gathered from natural token order):
+  // sb[i] is the address of the first row of the wave's i-th block.  The instruction offset moves the
+  // global and the LDS address together, so each base is handed over minus that offset.
+  __device__ __forceinline__ void issue_blocks(const char* const (&sb)[S::kLoadsPerThread], uint32_t lds_tile, int wave) const {
+#pragma unroll
+    for (int grp = 0; grp < kGroups; ++grp) {
+      const uint32_t m0 = lds_tile + (uint32_t)(wave * S::kLoadsPerThread + grp * 4) * 1024u;
+      asm volatile(
+          "s_mov_b32 m0, %[m0]\n\t"
+          "s_nop 0\n\t"
+          "global_load_lds_dwordx4 %[v0], %[s0] offset:0\n\t"
+          "global_load_lds_dwordx4 %[v1], %[s1] offset:1024\n\t"
+          "global_load_lds_dwordx4 %[v2], %[s2] offset:2048\n\t"
+          "global_load_lds_dwordx4 %[v3], %[s3] offset:3072\n\t"
+          :
+          : [m0] "s"(m0), [v0] "v"(voff[0]), [v1] "v"(voff[1]), [v2] "v"(voff[2]), [v3] "v"(voff[3]), [s0] "s"(sb[grp * 4]),
+            [s1] "s"(sb[grp * 4 + 1] - 1024), [s2] "s"(sb[grp * 4 + 2] - 2048), [s3] "s"(sb[grp * 4 + 3] - 3072)
+          : "memory");
+    }
+  }
+
+  // One block whose rows may run past the end of the tensor: lane rows are clamped to `last_row`
+  // (rows counted from `first`, which is inside the tensor).
+  __device__ __forceinline__ void issue_clamped(const char* first, int32_t last_row, int i, uint32_t lds_tile, int wave, int lane) const {
+    const int row = min(lane / S::kChunksPerRow, (int)last_row);
+    const uint32_t v = (voff[i & 3] % (uint32_t)S::kRowBytes) + (uint32_t)row * S::kRowBytes;
+    const uint32_t m0 = lds_tile + (uint32_t)(wave * S::kLoadsPerThread + i) * 1024u;
+    asm volatile(
+        "s_mov_b32 m0, %[m0]\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %[v], %[sb] offset:0\n\t"
+        :
+        : [m0] "s"(m0), [v] "v"(v), [sb] "s"(first)
+        : "memory");
+  }
 };
 
 // Exchange with the partner lane (lane ^ 32) on the VALU: returns max / sum of x and partner's x.

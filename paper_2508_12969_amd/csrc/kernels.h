@@ -40,6 +40,11 @@ struct AttnArgs {
   int64_t n;                   // tiles
   int32_t B, D;
   float scale;
+  // natural-order variant (bf16 kernels): q, k, v, out are [batch, heads, N_real, D] and the kernel gathers / scatters
+  int32_t natural;
+  const int32_t* tile_origin;  // device [n]; natural-order row of slot 0 of every tile
+  int32_t H, W, th, tw;
+  int64_t n_vid, N_real;
 };
 // fp32 problems, B <= 128, D in {32, 64, 128}
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);

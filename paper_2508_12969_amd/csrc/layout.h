@@ -31,6 +31,7 @@ struct DeviceTables {
   int32_t* dense_pair_walk = nullptr; // [n + 2] the walk 0..n-1 kept by both tiles (dense path)
   int32_t* tile_class = nullptr; // [n] index into class_mask; 0 = every slot holds a token
   SlotMask* class_mask = nullptr; // [num_classes]
+  int32_t* tile_origin = nullptr; // [n] natural-order row of slot 0 of every tile
 };
 
 }  // namespace ca
