@@ -182,12 +182,14 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   if (st != CA_OK) return st;
   if (natural) {
     const ca_problem& p = L->prob;
+    if (p.dtype != CA_BF16) return fail(CA_ERR_UNSUPPORTED, "natural-order attention is built for bf16 problems only");
     const int rows_per_block = 1024 / (p.head_dim * 2);
-    if (p.dtype != CA_BF16 || p.tw % rows_per_block != 0 || L->N_real >= ((int64_t)1 << 31)) {
-      set_error("natural-order attention needs bf16 and a tile width that is a multiple of %d tokens (head_dim %d); got tw=%d",
+    if (p.tw % rows_per_block != 0) {
+      set_error("natural-order attention needs a tile width that is a multiple of %d tokens at head_dim %d; got tw=%d",
                 rows_per_block, p.head_dim, p.tw);
       return CA_ERR_UNSUPPORTED;
     }
+    if (L->N_real >= ((int64_t)1 << 31)) return fail(CA_ERR_UNSUPPORTED, "natural-order attention needs fewer than 2^31 tokens");
   }
   st = ensure_uploaded(L);
   if (st != CA_OK) return st;

@@ -415,8 +415,7 @@ hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
   if (items > 0x7fffffff) return hipErrorInvalidValue;
   if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
   if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
-  if (a.B == 64 && a.D == 128 && !a.natural) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
-  if (a.B == 64 && a.D == 128) return launch<64, 128>(a, stream);
+  if (a.B == 64 && a.D == 128) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
   if (a.B == 64 && a.D == 64) return launch<64, 64>(a, stream);
   return hipErrorInvalidValue;
 }

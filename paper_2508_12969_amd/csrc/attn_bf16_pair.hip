@@ -27,6 +27,8 @@ struct PairShape {  // B = 64, D = 128, four waves
   static constexpr int kRowsPerLoad = 4;
 };
 
+// kNat: q, k, v, out in natural token order, gathered and scattered here (see attn_bf16.hip)
+template <bool kNat>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void attn_bf16_pair_kernel(AttnArgs a) {
   using S = PairShape;
@@ -60,9 +62,44 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const int64_t head = row_a / a.n;
   const int64_t tile_a = row_a - head * a.n, tile_b = has_b ? row_b - head * a.n : tile_a;
   const int64_t q_tile = member ? tile_b : tile_a;
-  const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
+  const int64_t plane = (batch * a.num_heads + head) * (kNat ? a.N_real * (int64_t)S::kRowBytes : a.n * (int64_t)S::kTileBytes);
   const char* Kp = static_cast<const char*>(a.k) + plane;
   const char* Vp = static_cast<const char*>(a.v) + plane;
+  const auto tile_origin = CONST_PTR(int32_t, a.tile_origin);
+  int32_t row_in_tile[kNat ? S::kLoadsPerThread : 1];  // natural order: row offset of each KiB block this wave copies
+  if constexpr (kNat) {
+#pragma unroll
+    for (int i = 0; i < S::kLoadsPerThread; ++i) {
+      const int slot0 = (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad;
+      const int dx = slot0 % a.tw, run = slot0 / a.tw, dy = run % a.th, dt = run / a.th;
+      row_in_tile[i] = (dt * a.H + dy) * a.W + dx;
+    }
+  }
+  auto issue_tile = [&](const auto& loader, const char* base, int tile, int32_t origin, uint32_t lds_addr) {
+    if constexpr (!kNat) {
+      loader.issue(base + (int64_t)tile * S::kTileBytes, lds_addr, wave);
+    } else {
+      const bool text = tile >= a.n_vid;
+      const char* sb[S::kLoadsPerThread];
+      bool inside = true;
+#pragma unroll
+      for (int i = 0; i < S::kLoadsPerThread; ++i) {
+        const int32_t row = origin + (text ? (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad : row_in_tile[i]);
+        inside = inside && row + S::kRowsPerLoad <= a.N_real;
+        sb[i] = base + (int64_t)row * S::kRowBytes;
+      }
+      if (inside) {
+        loader.issue_blocks(sb, lds_addr, wave);
+      } else {
+#pragma unroll
+        for (int i = 0; i < S::kLoadsPerThread; ++i) {
+          const int32_t row = origin + (text ? (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad : row_in_tile[i]);
+          const int32_t first = min(row, (int32_t)a.N_real - 1);
+          loader.issue_clamped(base + (int64_t)first * S::kRowBytes, (int32_t)a.N_real - 1 - first, i, lds_addr, wave, lane);
+        }
+      }
+    }
+  };
 
   // the pair's walk: one word per tile of the union of the two rows, ascending tile ids:
   // tile id | padding class << 24 | bit 30: kept by the first query tile | bit 31: by the second
@@ -78,7 +115,13 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const bool wave_active = q_valid != 0 && (member == 0 || has_b);
 
   // Q fragment: B operand of S^T, lane (qi, g) holds d = 16*step + 8*g .. +7 of its query.
-  const int64_t q_row = q_tile * S::B + block * 32 + qi;
+  int64_t q_row = q_tile * S::B + block * 32 + qi;
+  if constexpr (kNat) {
+    const int slot = block * 32 + qi;
+    const int dx = slot % a.tw, run = slot / a.tw, dy = run % a.th, dt = run / a.th;
+    const int64_t row = tile_origin[q_tile] + (q_tile >= a.n_vid ? slot : (dt * a.H + dy) * a.W + dx);
+    q_row = row < a.N_real ? row : a.N_real - 1;
+  }
   bf16x8 qf[S::kQkSteps];
   {
     const char* Qp = static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes + g * 16;
@@ -116,13 +159,15 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   // ---- the walk, with its words two steps ahead (the table is readable two words past its end) --
   int32_t word = walk[0], word1 = walk[1];
   if (count > 0) {
-    k_loader.issue(Kp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_k_addr, wave);
-    v_loader.issue(Vp + (int64_t)(word & 0xffffff) * S::kTileBytes, lds_v_addr, wave);
+    const int32_t origin = kNat ? tile_origin[word & 0xffffff] : 0;
+    issue_tile(k_loader, Kp, word & 0xffffff, origin, lds_k_addr);
+    issue_tile(v_loader, Vp, word & 0xffffff, origin, lds_v_addr);
   }
 
   for (int j = 0; j < count; ++j) {
     const int32_t word2 = walk[j + 2];
     const int next_tile = word1 & 0xffffff;
+    const int32_t next_origin = kNat ? tile_origin[next_tile] : 0;
     const bool more = j + 1 < count;
     const bool mine = wave_active && ((word >> (30 + member)) & 1);
     const int cls = (word >> 24) & 0x3f;
@@ -144,7 +189,7 @@ void attn_bf16_pair_kernel(AttnArgs a) {
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading K
-    if (more) k_loader.issue(Kp + (int64_t)next_tile * S::kTileBytes, lds_k_addr, wave);
+    if (more) issue_tile(k_loader, Kp, next_tile, next_origin, lds_k_addr);
 
     bf16x8 pf[S::kKeyBlocks][2];
     if (mine) {
@@ -233,7 +278,7 @@ void attn_bf16_pair_kernel(AttnArgs a) {
     }
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V
-    if (more) v_loader.issue(Vp + (int64_t)next_tile * S::kTileBytes, lds_v_addr, wave);
+    if (more) issue_tile(v_loader, Vp, next_tile, next_origin, lds_v_addr);
     word = word1;
     word1 = word2;
   }
@@ -244,6 +289,7 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const bool q_real = (q_valid >> qi) & 1u;
   const float inv = (q_real && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
   char* Op = static_cast<char*>(a.out) + plane + q_row * S::kRowBytes;
+  if (kNat && !q_real) return;  // natural order has no row for a padding slot
 #pragma unroll
   for (int db = 0; db < S::kDBlocks; ++db)
 #pragma unroll
@@ -262,7 +308,12 @@ hipError_t launch_attn_bf16_pair(const AttnArgs& a, hipStream_t stream) {
   const int64_t items = (int64_t)a.batch * a.num_pairs;
   if (items == 0) return hipSuccess;
   if (items > 0x7fffffff || a.B != 64 || a.D != 128 || !a.pair_rows) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attn_bf16_pair_kernel, dim3((unsigned)items), dim3(256), 0, stream, a);
+  if (a.natural) {
+    if (a.tw % PairShape::kRowsPerLoad != 0) return hipErrorInvalidValue;  // a KiB block must stay inside one run
+    hipLaunchKernelGGL(attn_bf16_pair_kernel<true>, dim3((unsigned)items), dim3(256), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL(attn_bf16_pair_kernel<false>, dim3((unsigned)items), dim3(256), 0, stream, a);
+  }
   return hipGetLastError();
 }
 
