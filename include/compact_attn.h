@@ -71,10 +71,15 @@ typedef struct {
 } ca_group;
 
 /* One head: up to CA_MAX_GROUPS groups, max_dt non-negative and strictly increasing.
- * Key tiles farther than the last group's max_dt are dropped.  num_groups = 0 keeps only text tiles. */
+ * Key tiles farther than the last group's max_dt are dropped.  num_groups = 0 keeps only text tiles.
+ * clamp_centre = 0: windows are centred on the query tile and clipped by the grid (Eq. 1 as written).
+ * clamp_centre = 1: a window keeps its full size at the border, the way sliding-tile windows do: on an
+ * axis of L tiles a window of radius r with 2r+1 < L is centred at min(max(q, r), L-1-r) instead of q,
+ * and a window with 2r+1 >= L covers the whole axis. */
 #define CA_MAX_GROUPS 8
 typedef struct {
   int32_t num_groups;
+  int32_t clamp_centre;
   const ca_group* groups; /* host pointer, read during compact_attn_build_layout only */
 } ca_head;
 

@@ -18,6 +18,11 @@ negative.  For a query tile (qt, qh, qw) and a key tile (kt, kh, kw):
 Readings taken where the paper is silent: radii in tile units, absolute
 distance between tile-frame indices, ascending tile ids inside a row.
 
+Variant (not in the paper's equations; the sliding-tile scheme it builds on
+does this): a `ClampedHead` keeps every window at its full 2r+1 tiles near a
+border by moving the window's centre inward, to min(max(q, r), L-1-r) on an
+axis of L tiles; a window of 2r+1 >= L tiles covers the whole axis.
+
 Three independent formulations live here so that they can be checked against
 each other: `keep_pair` (the rule on one pair), `kept_tiles` (enumeration of
 the two clipped boxes per key frame) and `row_count_closed_form`.
@@ -31,6 +36,23 @@ def window_present(win):
     return win[0] >= 0 and win[1] >= 0
 
 
+class ClampedHead(tuple):
+    """A head (tuple of groups) whose windows are moved inward at the border instead of clipped."""
+
+
+def is_clamped(head):
+    return isinstance(head, ClampedHead)
+
+
+def in_window(q, k, radius, length, clamped):
+    """Is position k inside the window of a query at position q on an axis of `length` tiles?"""
+    if not clamped:
+        return abs(k - q) <= radius
+    if 2 * radius + 1 >= length:
+        return True
+    return abs(k - min(max(q, radius), length - 1 - radius)) <= radius
+
+
 def check_head(head):
     """Validate one head's group list; returns it as a tuple of plain tuples."""
     out = []
@@ -41,7 +63,7 @@ def check_head(head):
             raise ValueError("max_dt must be non-negative and strictly increasing")
         last = max_dt
         out.append((int(max_dt), (int(a[0]), int(a[1])), (int(b[0]), int(b[1]))))
-    return tuple(out)
+    return ClampedHead(out) if is_clamped(head) else tuple(out)
 
 
 def group_of(head, dt):
@@ -61,8 +83,11 @@ def keep_pair(geom: Geometry, head, q_tile, k_tile):
     grp = group_of(head, abs(kt - qt))
     if grp is None:
         return False
+    c = is_clamped(head)
     for win in (grp[1], grp[2]):
-        if window_present(win) and abs(kh - qh) <= win[0] and abs(kw - qw) <= win[1]:
+        if not window_present(win):
+            continue
+        if in_window(qh, kh, win[0], geom.nH, c) and in_window(qw, kw, win[1], geom.nW, c):
             return True
     return False
 
@@ -81,6 +106,19 @@ def keep_mask_bruteforce(geom: Geometry, heads):
 def _clipped_box(center, radius, length):
     """Inclusive index range of |i - center| <= radius inside [0, length)."""
     return max(center - radius, 0), min(center + radius, length - 1)
+
+
+def _moved_box(center, radius, length):
+    """Inclusive index range of a window of 2*radius+1 tiles that contains `center` and stays inside
+    [0, length): pushed right from a negative start, pushed left from an overhanging end."""
+    if 2 * radius + 1 >= length:
+        return 0, length - 1
+    lo, hi = center - radius, center + radius
+    if lo < 0:
+        lo, hi = 0, 2 * radius
+    if hi > length - 1:
+        lo, hi = length - 1 - 2 * radius, length - 1
+    return lo, hi
 
 
 def kept_tiles(geom: Geometry, head, q_tile):
@@ -102,8 +140,9 @@ def kept_tiles(geom: Geometry, head, q_tile):
         for win in (grp[1], grp[2]):
             if not window_present(win):
                 continue
-            h0, h1 = _clipped_box(qh, win[0], geom.nH)
-            w0, w1 = _clipped_box(qw, win[1], geom.nW)
+            box = _moved_box if is_clamped(head) else _clipped_box
+            h0, h1 = box(qh, win[0], geom.nH)
+            w0, w1 = box(qw, win[1], geom.nW)
             for kh in range(h0, h1 + 1):
                 for kw in range(w0, w1 + 1):
                     frame.add(geom.tile_id(kt, kh, kw))
@@ -124,35 +163,37 @@ def build_csr(geom: Geometry, heads):
     return out
 
 
-def _count_1d(center, radius, length):
-    lo, hi = _clipped_box(center, radius, length)
-    return hi - lo + 1
+def _range_1d(q, radius, length, clamped):
+    """(lo, hi) of a window on one axis: clipped around q, or of full size 2r+1 moved inward."""
+    if clamped:
+        size = min(2 * radius + 1, length)
+        lo = min(max(q - radius, 0), length - size)
+        return lo, lo + size - 1
+    return max(q - radius, 0), min(q + radius, length - 1)
 
 
-def _box_count(geom, qh, qw, win):
-    if not window_present(win):
-        return 0
-    return _count_1d(qh, win[0], geom.nH) * _count_1d(qw, win[1], geom.nW)
+def _overlap(r1, r2):
+    return max(0, min(r1[1], r2[1]) - max(r1[0], r2[0]) + 1)
 
 
 def row_count_closed_form(geom: Geometry, head, q_tile):
-    """Number of kept key tiles of a row by inclusion-exclusion on the two boxes.
-
-    Both boxes share the centre, so their intersection is the box with the
-    smaller radius on each axis (absent when either window is absent).
-    """
+    """Number of kept key tiles of a row by inclusion-exclusion on the two boxes: |A| + |B| - |A and B|,
+    every box a product of two index ranges (written without the helper the enumeration uses)."""
     if q_tile >= geom.n_vid:
         return geom.n
     head = check_head(head)
+    c = is_clamped(head)
     qt, qh, qw = geom.tile_coords(q_tile)
     total = geom.n_txt
     for kt in range(geom.nT):
         grp = group_of(head, abs(kt - qt))
         if grp is None:
             continue
-        a, b = grp[1], grp[2]
-        both = (min(a[0], b[0]), min(a[1], b[1])) if window_present(a) and window_present(b) else (-1, -1)
-        total += _box_count(geom, qh, qw, a) + _box_count(geom, qh, qw, b) - _box_count(geom, qh, qw, both)
+        boxes = [(_range_1d(qh, w[0], geom.nH, c), _range_1d(qw, w[1], geom.nW, c)) for w in (grp[1], grp[2]) if window_present(w)]
+        for hr, wr in boxes:
+            total += _overlap(hr, hr) * _overlap(wr, wr)
+        if len(boxes) == 2:
+            total -= _overlap(boxes[0][0], boxes[1][0]) * _overlap(boxes[0][1], boxes[1][1])
     return total
 
 

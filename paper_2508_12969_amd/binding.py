@@ -52,7 +52,7 @@ class ca_group(ctypes.Structure):
 
 
 class ca_head(ctypes.Structure):
-    _fields_ = [("num_groups", ctypes.c_int32), ("groups", ctypes.POINTER(ca_group))]
+    _fields_ = [("num_groups", ctypes.c_int32), ("clamp_centre", ctypes.c_int32), ("groups", ctypes.POINTER(ca_group))]
 
 
 class ca_problem(ctypes.Structure):
@@ -157,8 +157,9 @@ class Layout:
         return (p.batch, p.num_heads, self.n_tokens_padded if padded else self.n_tokens_real, p.head_dim)
 
 
-def compact_attn_build_layout(T, H, W, tile, n_text, batch, num_heads, head_dim, dtype, heads, scale=0.0):
-    """heads: per head a list of (max_dt, (rh, rw), (rh, rw)); dtype "f32" or "bf16"."""
+def compact_attn_build_layout(T, H, W, tile, n_text, batch, num_heads, head_dim, dtype, heads, scale=0.0, clamp_centre=False):
+    """heads: per head a list of (max_dt, (rh, rw), (rh, rw)); dtype "f32" or "bf16".
+    clamp_centre: one flag for all heads or one per head: windows keep their size at the border."""
     lib = load_library()
     if len(heads) != num_heads:
         raise ValueError("one head description per head is required")
@@ -172,6 +173,7 @@ def compact_attn_build_layout(T, H, W, tile, n_text, batch, num_heads, head_dim,
             arr[j] = ca_group(max_dt, ca_window(*a), ca_window(*b))
         keep.append(arr)
         c_heads[i].num_groups = len(groups)
+        c_heads[i].clamp_centre = int(clamp_centre[i] if isinstance(clamp_centre, (list, tuple)) else clamp_centre)
         c_heads[i].groups = ctypes.cast(arr, ctypes.POINTER(ca_group))
     handle = ctypes.c_void_p()
     _check(lib.compact_attn_build_layout(ctypes.byref(prob), c_heads, ctypes.byref(handle)))

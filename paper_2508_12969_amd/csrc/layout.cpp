@@ -40,12 +40,22 @@ inline Interval clip(int32_t center, int32_t radius, int32_t len) {
   return {(int32_t)std::max<int64_t>(lo, 0), (int32_t)std::min<int64_t>(hi, len - 1)};
 }
 
+// Tiles of one axis a window covers: clipped around the query, or (clamp) moved inward so that it
+// keeps its 2*radius+1 tiles (the whole axis if that is shorter).
+inline Interval window_range(int32_t center, int32_t radius, int32_t len, bool clamp) {
+  if (!clamp) return clip(center, radius, len);
+  if (2 * (int64_t)radius + 1 >= len) return {0, len - 1};
+  const int32_t c = std::min(std::max(center, radius), len - 1 - radius);
+  return {c - radius, c + radius};
+}
+
 inline bool present(const ca_window& w) { return w.rh >= 0 && w.rw >= 0; }
 
 // Resolved windows of one head for every tile-frame distance 0..nT-1 (group lookup done once).
 struct HeadPlan {
   std::vector<int8_t> has;      // [nT] distance covered by some group
   std::vector<ca_window> a, b;  // [nT]
+  bool clamp = false;           // windows keep their size at the border (centre moved inward)
 };
 
 int plan_head(const ca_head& h, int32_t head_index, int32_t nT, HeadPlan& plan) {
@@ -66,6 +76,11 @@ int plan_head(const ca_head& h, int32_t head_index, int32_t nT, HeadPlan& plan) 
     }
     last = h.groups[g].max_dt;
   }
+  if (h.clamp_centre != 0 && h.clamp_centre != 1) {
+    set_error("head %d: clamp_centre must be 0 or 1", head_index);
+    return CA_ERR_INVALID_ARG;
+  }
+  plan.clamp = h.clamp_centre == 1;
   plan.has.assign(nT, 0);
   plan.a.assign(nT, ca_window{-1, -1});
   plan.b.assign(nT, ca_window{-1, -1});
@@ -90,8 +105,8 @@ inline void for_each_run(const ca_layout& L, const HeadPlan& plan, int32_t qt, i
     const bool pa = present(wa), pb = present(wb);
     if (!pa && !pb) continue;
     Interval ha{0, -1}, hb{0, -1}, ca_{0, -1}, cb{0, -1};
-    if (pa) { ha = clip(qh, wa.rh, L.nH); ca_ = clip(qw, wa.rw, L.nW); }
-    if (pb) { hb = clip(qh, wb.rh, L.nH); cb = clip(qw, wb.rw, L.nW); }
+    if (pa) { ha = window_range(qh, wa.rh, L.nH, plan.clamp); ca_ = window_range(qw, wa.rw, L.nW, plan.clamp); }
+    if (pb) { hb = window_range(qh, wb.rh, L.nH, plan.clamp); cb = window_range(qw, wb.rw, L.nW, plan.clamp); }
     const int32_t h_lo = pa && pb ? std::min(ha.lo, hb.lo) : (pa ? ha.lo : hb.lo);
     const int32_t h_hi = pa && pb ? std::max(ha.hi, hb.hi) : (pa ? ha.hi : hb.hi);
     for (int32_t kh = h_lo; kh <= h_hi; ++kh) {
@@ -101,7 +116,7 @@ inline void for_each_run(const ca_layout& L, const HeadPlan& plan, int32_t qt, i
       if (in_a && in_b) { lo = std::min(ca_.lo, cb.lo); hi = std::max(ca_.hi, cb.hi); }
       else if (in_a) { lo = ca_.lo; hi = ca_.hi; }
       else if (in_b) { lo = cb.lo; hi = cb.hi; }
-      else continue;  // rows between two disjoint height ranges cannot occur (both contain qh), kept for safety
+      else continue;  // rows between two disjoint height ranges cannot occur (both contain qh, clamped or not), kept for safety
       const int64_t first = ((int64_t)kt * L.nH + kh) * L.nW + lo;
       emit((int32_t)first, hi - lo + 1);
     }

@@ -96,6 +96,15 @@ def test_random_small_layouts_bit_exact(case):
         assert np.array_equal(row_ptr, want[h][0]) and np.array_equal(col_idx, want[h][1])
     assert np.array_equal(ca.compact_attn_layout_order(lay), OL.work_order(OL.row_counts(g, heads)))
     lay.free()
+    # the same heads with windows that keep their size at the border (flag per head: first on, rest off)
+    flags = [h == 0 for h in range(len(heads))]
+    lay = ca.compact_attn_build_layout(T, H, W, tile, n_text, 1, len(heads), 8, "f32", heads, clamp_centre=flags)
+    moved = [OL.ClampedHead(head) if f else head for head, f in zip(heads, flags)]
+    want = OL.build_csr(g, moved)
+    for h in range(len(heads)):
+        row_ptr, col_idx = ca.compact_attn_layout_csr(lay, h)
+        assert np.array_equal(row_ptr, want[h][0]) and np.array_equal(col_idx, want[h][1])
+    lay.free()
 
 
 def test_huge_radius_and_many_groups():
@@ -126,6 +135,7 @@ def test_invalid_arguments_are_rejected_on_the_host():
     _expect_error(binding.CA_ERR_INVALID_ARG, heads=[[(-1, (0, 0), ABSENT)]])
     _expect_error(binding.CA_ERR_INVALID_ARG, heads=[[(i, (0, 0), ABSENT) for i in range(9)]])
     _expect_error(binding.CA_ERR_INVALID_ARG, scale=float("nan"))
+    _expect_error(binding.CA_ERR_INVALID_ARG, clamp_centre=2)
     lib = ca.load_library()
     assert lib.compact_attn_build_layout(None, None, None) == binding.CA_ERR_INVALID_ARG
     assert lib.compact_attn_layout_info(None, None, None, None, None, None) == binding.CA_ERR_INVALID_ARG

@@ -131,6 +131,26 @@ def test_padded_grids_text_and_odd_heads(shape):
     _say(_full_parity(wl, scale=0.05))
 
 
+def test_windows_that_keep_their_size_at_the_border():
+    """Heads with clamp_centre set: the layout moves windows inward at the border (checked bit for
+    bit on the host); here the kernels run such a layout and match the oracle's rule."""
+    from oracle import layout as OLay
+    _say("clamped windows")
+    heads = [[(0, (1, 1), ABSENT), (1, (0, 0), ABSENT)], [(2, (0, 2), (1, 0))]]
+    wl = make_workload("clamped", 5, 29, 40, (2, 8, 8), 128, len(heads), 128, "bf16", heads)
+    g = geometry_of(wl)
+    lay = ca.compact_attn_build_layout(wl.T, wl.H, wl.W, wl.tile, wl.n_text, 1, len(heads), 128, "bf16", heads,
+                                       clamp_centre=[True, True])
+    plain = build_layout(ca, wl)
+    assert lay.nnz_total > plain.nnz_total                  # border rows gained tiles
+    q, k, v = make_qkv(wl, DEV, q_gain=2.0)
+    out, _ = gpu_attention(ca, wl, lay, q, k, v)
+    torch.cuda.synchronize()
+    moved = [OLay.ClampedHead(h) for h in heads]
+    want = OA.masked_attention(g, moved, to_f64(q[0]), to_f64(k[0]), to_f64(v[0]))
+    _say(compare(to_f64(out[0]), want, *tolerances("bf16"), what="clamped windows"))
+
+
 def test_no_text_and_empty_rows_give_zeros():
     _say("empty rows")
     heads = [[(0, ABSENT, ABSENT)], [(0, (0, 0), ABSENT)]]

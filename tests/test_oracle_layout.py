@@ -152,6 +152,40 @@ def test_three_formulations_agree(case):
         assert np.all(np.diff(cols) > 0)
 
 
+@settings(max_examples=120, deadline=None)
+@given(_cases())
+def test_three_formulations_agree_with_clamped_centres(case):
+    g, head = case
+    head = L.ClampedHead(head)
+    mask = L.keep_mask_bruteforce(g, [head])[0]
+    clipped = L.keep_mask_bruteforce(g, [list(head)])[0]
+    assert np.all(mask >= clipped)                     # moving a window inward never loses a clipped tile
+    for q in range(g.n):
+        cols = L.kept_tiles(g, head, q)
+        assert np.array_equal(cols, np.nonzero(mask[q])[0])
+        assert L.row_count_closed_form(g, head, q) == len(cols)
+
+
+def test_clamped_centres_hand_worked():
+    # one frame, one tile row, six tile columns; radius 1 along w
+    g = Geometry(1, 1, 6, 1, 1, 1, 0)
+    clipped = [(0, (0, 1), ABSENT)]
+    assert [L.kept_tiles(g, clipped, q).tolist() for q in range(6)] == [[0, 1], [0, 1, 2], [1, 2, 3], [2, 3, 4], [3, 4, 5], [4, 5]]
+    clamped = L.ClampedHead(clipped)
+    assert [L.kept_tiles(g, clamped, q).tolist() for q in range(6)] == [[0, 1, 2], [0, 1, 2], [1, 2, 3], [2, 3, 4], [3, 4, 5], [3, 4, 5]]
+    # radius 3 needs 7 columns: longer than the axis, the window covers it from every query
+    wide = L.ClampedHead([(0, (0, 3), ABSENT)])
+    assert all(L.kept_tiles(g, wide, q).tolist() == list(range(6)) for q in range(6))
+    # a window that fits has its full size in every row: (2*1+1) * (2*2+1) tiles per kept frame
+    g = Geometry(3, 5, 7, 1, 1, 1, 0)
+    head = L.ClampedHead([(1, (1, 2), ABSENT)])
+    frames = lambda q: 2 if g.tile_coords(q)[0] in (0, g.nT - 1) else 3
+    assert all(L.row_count_closed_form(g, head, q) == 15 * frames(q) for q in range(g.n))
+    # two windows of one group get different centres near a border and still both contain the query
+    head = L.ClampedHead([(0, (0, 2), (1, 0))])
+    assert L.kept_tiles(g, head, 0).tolist() == [0, 1, 2, 3, 4, 7, 14]
+
+
 def test_work_order_is_descending_count_with_stable_ties():
     rng = np.random.default_rng(3)
     counts = rng.integers(0, 6, size=(5, 37))
