@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # script scaled by a 1 GiB device copy in the same run (profiles/attn_bf16_kernel_*_pmc.md holds
 # the counters and the command).  A counter run is a separate profiler pass, so the figure is a
 # recorded measurement, not one taken live; workloads without a committed counter run report null.
-MEASURED_TRAFFIC_BYTES = {"cfg4-S65": 102.4e9}
+MEASURED_TRAFFIC_BYTES = {"cfg4-S65": 116.4e9, "cfg3": 62.6e9}
 
 
 def parse():
