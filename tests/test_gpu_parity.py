@@ -208,6 +208,11 @@ def _sampled_parity(name, heads_to_check, dense=False):
     q, k, v = make_qkv(wl, DEV)
     out, _ = gpu_attention(ca, wl, lay, q, k, v, dense=dense)
     torch.cuda.synchronize()
+    if not dense:       # the same at full size with the gather / scatter inside the kernel: every bit equal
+        fused = ca.compact_attn_forward_natural(q, k, v, lay)
+        torch.cuda.synchronize()
+        assert torch.equal(fused, out), f"{name}: natural-order forward differs from the permuted path"
+        del fused
     counts = OL.row_counts(g, wl.heads)
     tok_tile, _ = g.token_tile_and_slot()
     rng = np.random.default_rng(2508)
