@@ -508,6 +508,8 @@ def test_batch_of_three(dtype, D, tile):
     dense, _ = gpu_attention(ca, wl, lay, q, k, v, dense=True)
     torch.cuda.synchronize()
     assert not torch.equal(out[0], out[1])
+    if dtype == "bf16":
+        assert torch.equal(ca.compact_attn_forward_natural(q, k, v, lay), out)
     full = [[(g.nT - 1, (g.nH - 1, g.nW - 1), ABSENT)]] * len(heads)
     for b in range(3):
         want = OA.masked_attention(g, heads, to_f64(q[b]), to_f64(k[b]), to_f64(v[b]))
