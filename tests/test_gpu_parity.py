@@ -455,6 +455,8 @@ def test_pattern_families_end_to_end():
     (128, (3, 13, 20), (1, 8, 8), 64),        # B=64 D=128 (paired kernel)
     (64, (3, 9, 16), (1, 8, 8), 0),           # B=64 D=64
     (128, (4, 7, 12), (4, 8, 4), 0),          # tile width 4 = one block per run
+    (128, (3, 9, 40), (1, 4, 16), 64),        # wide tiles: four blocks per run, B=64
+    (64, (3, 5, 40), (2, 4, 16), 0),          # B=128 D=64, two 8-token blocks per run
 ])
 def test_forward_natural_order(shape):
     """compact_attn_forward_natural reads q, k, v in natural order and writes natural order: same
