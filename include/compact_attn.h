@@ -188,7 +188,9 @@ int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout*
  * order and scatters the output rows back, so no compact_attn_permute pass is needed).
  *   q, k, v, out: device pointers, [batch, heads, N_real, D] in natural order; out must not alias
  *   q/k/v.  Every row of out is written (zeros for a query whose kept set holds no real key).
- * Same arithmetic per query as compact_attn_forward.  Supported: bf16 with (B, D) as for
+ * Same arithmetic per query as compact_attn_forward, bit for bit, provided k and v hold finite
+ * values: the padding slots of edge tiles, which the tile-order tensors hold as zeros, alias other
+ * rows of the tensor here and enter the products with weight zero.  Supported: bf16 with (B, D) as for
  * compact_attn_forward and a tile width tw that is a multiple of 1024 / (2*D) tokens (4 for D = 128,
  * 8 for D = 64); otherwise CA_ERR_UNSUPPORTED. */
 int compact_attn_forward_natural(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
