@@ -23,10 +23,14 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
 # HBM bytes of one forward launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs of this
-# script scaled by a 1 GiB device copy in the same run (profiles/attn_bf16_kernel_*_pmc.md holds
-# the counters and the command).  A counter run is a separate profiler pass, so the figure is a
-# recorded measurement, not one taken live; workloads without a committed counter run report null.
-MEASURED_TRAFFIC_BYTES = {"cfg4-S65": 116.4e9, "cfg3": 62.6e9}
+# script scaled by a 1 GiB device copy in the same run.  A counter run is a separate profiler pass,
+# so the figure is a recorded measurement, not one taken live: it is printed with the summary file
+# it comes from, and as null for a workload without a committed counter run.
+RECORDED_TRAFFIC = {
+    "cfg4-S65": {"bytes": 116.4e9, "source": "profiles/attn_bf16_kernel_cfg4-S65_pmc.md"},
+    "cfg3": {"bytes": 62.6e9, "source": "profiles/attn_bf16_pair_kernel_cfg3.md"},
+}
+OTHER_CONFIGS = ("cfg4-S50", "cfg4-S80", "cfg3", "cfg5")
 
 
 def parse():
@@ -47,7 +51,9 @@ def parse():
     ap.add_argument("--pattern-report", action="store_true",
                     help="also search masks under the three pattern families of Table 3 on structured synthetic heads "
                          "and report the sparsity each family reaches")
-    ap.add_argument("--sweep", action="store_true", help="also time the forward kernel on the other cfg4 sparsities")
+    ap.add_argument("--other-calls", type=int, default=5,
+                    help="timed sparse forward calls on each of the other configurations (cfg4 at 50 %% and 80 %% "
+                         "sparsity, cfg3, cfg5), each with the dense kernel at the same shape beside it (0 = skip)")
     return ap.parse_args()
 
 
@@ -276,26 +282,47 @@ def main():
         except ca.CompactAttnError as exc:
             fused = {"unsupported": str(exc)}
 
-    sweep = {}
-    if args.sweep:
-        for name in ("cfg4-S50", "cfg4-S65", "cfg4-S80"):
+    def median_ms(fn, calls):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(calls):
+            a, b = ev(), ev()
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts)[len(ts) // 2]
+
+    # The other configurations: the forward and the dense kernel alone, on tile-ordered tensors.
+    others = {}
+    if args.other_calls > 0:
+        del out
+        for name in OTHER_CONFIGS:
             w2 = get_workload(name)
             l2 = layout_of(w2)
-            for _ in range(2):
-                ca.compact_attn_forward(qp, kp, vp, l2, out=op)
-            torch.cuda.synchronize()
-            ts = []
-            for _ in range(5):
-                a, b = ev(), ev()
-                a.record()
-                ca.compact_attn_forward(qp, kp, vp, l2, out=op)
-                b.record()
-                torch.cuda.synchronize()
-                ts.append(a.elapsed_time(b))
-            ms = sorted(ts)[len(ts) // 2]
-            f2 = l2.nnz_total * 4.0 * B * B * D
-            sweep[name] = {"ms": ms, "tflops": f2 / ms / 1e9, "kept": l2.nnz_total / (w2.num_heads * n ** 2),
-                           "speedup_vs_dense": (dense_ms / ms) if dense_ms else None}
+            ca.compact_attn_layout_upload(l2)
+            if w2.cfg != wl.cfg:
+                del qp, kp, vp, op
+                torch.cuda.empty_cache()
+                q2, k2, v2 = make_qkv(w2, dev)
+                qp, kp, vp = (ca.compact_attn_permute(t, l2) for t in (q2, k2, v2))
+                op = torch.empty_like(qp)
+                del q2, k2, v2
+            B2, D2, n2 = l2.tokens_per_tile, w2.head_dim, l2.n_tiles
+            ms = median_ms(lambda: ca.compact_attn_forward(qp, kp, vp, l2, out=op), args.other_calls)
+            same_shape = w2.cfg == wl.cfg and dense_ms is not None
+            d_ms = dense_ms if same_shape else median_ms(lambda: ca.compact_attn_dense(qp, kp, vp, l2, out=op), 1)
+            f2 = l2.nnz_total * w2.batch * 4.0 * B2 * B2 * D2
+            kept2 = l2.nnz_total / (w2.num_heads * n2 * n2)
+            ex2 = executed_fraction(ca, l2, w2)
+            others[name] = {"ms": ms, "tflops": f2 / ms / 1e9, "frac_bf16_mfma_peak": f2 / ms / 1e9 / PEAK_BF16_TFLOPS,
+                            "frac_executed": ex2 * f2 / ms / 1e9 / PEAK_BF16_TFLOPS,
+                            "kernel": "attn_bf16_pair_kernel" if (B2, D2) == (64, 128) else "attn_bf16_kernel",
+                            "kept_tile_fraction": kept2, "ideal_speedup": 1.0 / kept2,
+                            "dense_ms": d_ms, "dense_tflops": w2.num_heads * w2.batch * n2 * n2 * 4.0 * B2 * B2 * D2 / d_ms / 1e9,
+                            "speedup_vs_dense": d_ms / ms}
             l2.free()
 
     if args.calibrate_copy:
@@ -327,15 +354,17 @@ def main():
         "permute": {"ms_q_k_v": perm3_avg, "gbps": perm_bytes / perm3_avg / 1e6, "pct_hbm_peak": perm_bytes / perm3_avg / 1e6 / 8000 * 100},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_pair_kernel" if (B, D) == (64, 128) else "attn_bf16_kernel", "achieved": flops / fwd_avg / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "frac_executed": executed * flops / fwd_avg / 1e9 / PEAK_BF16_TFLOPS,
+                     "traffic": RECORDED_TRAFFIC.get(wl.name, {}).get("bytes"),
+                     "traffic_source": RECORDED_TRAFFIC.get(wl.name, {}).get("source"),
                      "algorithmic_flops_per_launch": flops,
                      "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * lay.n_tokens_padded * D * esz},
         "tile_mass": mass,
         "fused_gather_scatter": fused,
         "cpu_baseline": cpu,
     }
-    if sweep:
-        rec["sweep"] = sweep
+    if others:
+        rec["other_configs"] = others
     if args.pattern_report:
         rec["patterns"] = pattern_report(ca, dev)
     print(json.dumps(rec))

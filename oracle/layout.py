@@ -25,7 +25,10 @@ axis of L tiles; a window of 2r+1 >= L tiles covers the whole axis.
 
 Three independent formulations live here so that they can be checked against
 each other: `keep_pair` (the rule on one pair), `kept_tiles` (enumeration of
-the two clipped boxes per key frame) and `row_count_closed_form`.
+the two clipped boxes per key frame) and `row_count_closed_form`.  `keep_mask`
+evaluates the pair rule on coordinate arrays of all tile pairs of a head at
+once, for full-size grids where a loop over pairs would take hours; it is
+pinned to the other three.
 """
 import numpy as np
 
@@ -100,6 +103,42 @@ def keep_mask_bruteforce(geom: Geometry, heads):
         for q in range(geom.n):
             for k in range(geom.n):
                 mask[h, q, k] = keep_pair(geom, head, q, k)
+    return mask
+
+
+def keep_mask(geom: Geometry, head):
+    """bool[n, n] of one head: mask[q, k] = the pair rule of Sec. 4.1 for query tile q and key tile k,
+    evaluated on arrays of tile coordinates (every pair at once instead of one pair per call)."""
+    clamped = is_clamped(head)
+    head = check_head(head)
+    n, nv = geom.n, geom.n_vid
+    ids = np.arange(nv)
+    w = ids % geom.nW
+    h = (ids // geom.nW) % geom.nH
+    t = ids // (geom.nW * geom.nH)
+
+    def axis_inside(pos, radius, length):
+        q, k = pos[:, None], pos[None, :]
+        if not clamped:
+            return np.abs(k - q) <= radius
+        if 2 * radius + 1 >= length:
+            return np.ones((nv, nv), dtype=bool)
+        centre = np.minimum(np.maximum(q, radius), length - 1 - radius)
+        return np.abs(k - centre) <= radius
+
+    dt = np.abs(t[None, :] - t[:, None])
+    video = np.zeros((nv, nv), dtype=bool)
+    decided = np.zeros((nv, nv), dtype=bool)          # pairs whose frame distance an earlier group covers
+    for max_dt, win_a, win_b in head:
+        mine = (dt <= max_dt) & ~decided
+        decided |= dt <= max_dt
+        inside = np.zeros((nv, nv), dtype=bool)
+        for win in (win_a, win_b):
+            if window_present(win):
+                inside |= axis_inside(h, win[0], geom.nH) & axis_inside(w, win[1], geom.nW)
+        video |= mine & inside
+    mask = np.ones((n, n), dtype=bool)                 # text rows keep everything, text columns are always kept
+    mask[:nv, :nv] = video
     return mask
 
 

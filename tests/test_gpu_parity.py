@@ -261,6 +261,61 @@ def test_config5_sampled_rows():
     _sampled_parity("cfg5", [4, 6, 13, 17])
 
 
+def test_config4_sparsity50_sampled_rows():
+    _say("cfg4-S50 sampled")
+    _sampled_parity("cfg4-S50", [0, 4, 9, 15, 21])          # cross, local, global + local tail, wide local, thick cross
+
+
+def test_config4_sparsity80_sampled_rows():
+    _say("cfg4-S80 sampled")
+    _sampled_parity("cfg4-S80", [6, 11, 13, 17, 19])        # G/4/6, G/0/2, C0/0/2, full, L2/2/3
+
+
+# ---------------------------------------------------------------- full-size configs, every row (closed form)
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4-S50", "cfg4-S65", "cfg4-S80", "cfg5"])
+def test_every_row_at_full_size_zero_query_probe(name):
+    """Every real query row of every head at the benchmark sizes, sparse and dense, in the launch
+    configuration the benchmark times.  Q = 0 makes the softmax uniform over exactly the kept real
+    keys (Appendix D: softmax over the kept blocks; Sec. 4.1: the keep rule), so with V = indicator of
+    (key tile mod D) the output row is the kept real-token count per class over the total: a closed
+    form from the oracle's tile mask alone, which pins the walked tile list, the padding-key
+    masking, the launch-order remapping and its remainder, and the paired walk at scale."""
+    wl = get_workload(name)
+    _say("all rows", name)
+    g = geometry_of(wl)
+    D = wl.head_dim
+    lay = build_layout(ca, wl)
+    tok_tile = g.token_slots() // g.B                       # natural order -> tile id
+    real_per_tile = np.bincount(tok_tile, minlength=g.n).astype(np.float64)
+    onehot = np.zeros((g.n, D))
+    onehot[np.arange(g.n), np.arange(g.n) % D] = real_per_tile
+    tile_dev = torch.from_numpy(tok_tile).to(DEV)
+    q = torch.zeros(1, wl.num_heads, g.N_real, D, dtype=torch.bfloat16, device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(11)
+    k = torch.randn(1, wl.num_heads, g.N_real, D, device=DEV, generator=gen).to(torch.bfloat16)
+    v1 = torch.zeros(g.N_real, D, dtype=torch.bfloat16, device=DEV)
+    v1[torch.arange(g.N_real, device=DEV), tile_dev % D] = 1.0
+    v = v1[None, None].expand(1, wl.num_heads, -1, -1).contiguous()
+    del v1
+    out, _ = gpu_attention(ca, wl, lay, q, k, v)
+    dense, _ = gpu_attention(ca, wl, lay, q, k, v, dense=True)
+    torch.cuda.synchronize()
+    del q, k, v
+    want_dense = torch.from_numpy(onehot.sum(axis=0) / real_per_tile.sum()).to(DEV).float()
+    worst = 0.0
+    for h in range(wl.num_heads):
+        mask = OL.keep_mask(g, wl.heads[h]).astype(np.float64)
+        want = (mask @ onehot) / (mask @ real_per_tile)[:, None]            # [n, D] per query tile
+        want_rows = torch.from_numpy(want).to(DEV).float()[tile_dev]         # [N_real, D]
+        err = (out[0, h].float() - want_rows).abs().max().item()
+        err_d = (dense[0, h].float() - want_dense[None]).abs().max().item()
+        worst = max(worst, err, err_d)
+        assert err < 6e-3 and err_d < 6e-3, (name, h, err, err_d)
+    _say(name, "worst abs err over all rows", worst)
+
+
 # ---------------------------------------------------------------- exponent reference moves
 
 @pytest.mark.parametrize("shape", [("bf16", 128, (2, 8, 8)), ("bf16", 128, (1, 8, 8)), ("bf16", 64, (2, 8, 8))])

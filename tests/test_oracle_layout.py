@@ -291,3 +291,47 @@ def test_pair_table_invariants_on_random_masks():
         assert int(first[0][1] - first[0][0]) == g.nH * g.nW
         if g.nH >= 2:
             assert int(first[1][1] - first[1][0]) == g.nW
+
+
+# ---------------------------------------------------------------- keep_mask (all pairs of a head at once)
+
+def test_keep_mask_hand_worked_rows():
+    g = Geometry(1, 3, 3, 1, 1, 1)
+    m = L.keep_mask(g, [(0, (0, 2), (2, 0))])                           # full row + full column
+    assert np.nonzero(m[4])[0].tolist() == [1, 3, 4, 5, 7]
+    assert np.nonzero(m[0])[0].tolist() == [0, 1, 2, 3, 6]
+    m = L.keep_mask(g, [(0, (0, 1), ABSENT)])                           # rh=0, rw=1: an rh/rw swap gives [1,4,7]
+    assert np.nonzero(m[4])[0].tolist() == [3, 4, 5]
+    g = Geometry(4, 1, 2, 1, 1, 1)
+    far = [(0, (0, 0), ABSENT), (1, ABSENT, ABSENT), (3, (0, 1), ABSENT)]   # the first covering group decides
+    assert np.nonzero(L.keep_mask(g, far)[0])[0].tolist() == [0, 4, 5, 6, 7]
+    g = Geometry(2, 2, 2, 1, 2, 2, n_text=8)
+    m = L.keep_mask(g, [(0, (0, 0), ABSENT)])
+    assert m.astype(int).tolist() == [[1, 0, 1, 1], [0, 1, 1, 1], [1, 1, 1, 1], [1, 1, 1, 1]]
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.data())
+def test_keep_mask_equals_pair_rule_on_random_heads(data):
+    T, H, W = (data.draw(st.integers(1, 4)), data.draw(st.integers(1, 9)), data.draw(st.integers(1, 9)))
+    tt, th, tw = (data.draw(st.integers(1, 2)), data.draw(st.integers(1, 3)), data.draw(st.integers(1, 3)))
+    g = Geometry(T, H, W, tt, th, tw, n_text=data.draw(st.integers(0, 2)) * tt * th * tw)
+    win = st.tuples(st.integers(-1, 4), st.integers(-1, 4))
+    bounds = sorted(data.draw(st.sets(st.integers(0, 4), min_size=0, max_size=3)))
+    head = [(b, data.draw(win), data.draw(win)) for b in bounds]
+    if data.draw(st.booleans()):
+        head = L.ClampedHead(head)
+    assert np.array_equal(L.keep_mask(g, head), L.keep_mask_bruteforce(g, [head])[0])
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4-S50", "cfg4-S65", "cfg4-S80", "cfg5"])
+def test_keep_mask_reproduces_tabulated_counts_and_sampled_rows(name):
+    wl = get_workload(name)
+    g = _geom(wl)
+    rng = np.random.default_rng(7)
+    for h in range(wl.num_heads):
+        m = L.keep_mask(g, wl.heads[h])
+        assert int(m.sum()) == wl.expected_nnz[h]
+        for q in rng.choice(g.n, 3, replace=False).tolist() + [0, g.n_vid - 1, g.n - 1]:
+            assert np.array_equal(np.nonzero(m[q])[0], L.kept_tiles(g, wl.heads[h], q))
+            assert int(m[q].sum()) == L.row_count_closed_form(g, wl.heads[h], q)
