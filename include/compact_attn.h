@@ -19,7 +19,10 @@
  *   - Tensors are contiguous [batch, num_heads, N, head_dim], element type
  *     ca_problem.dtype.  N = N_real (natural order) or N_pad (tile order), see below.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
- *     calls enqueue work on it and return without synchronising.
+ *     calls enqueue work on it and return without synchronising, with one exception: the first
+ *     compute call that uses a layout not yet passed to compact_attn_layout_upload allocates and
+ *     copies that layout's device tables synchronously (and fails with CA_ERR_INVALID_ARG if
+ *     `stream` is being captured at that moment).
  *   - Failures detected on the host leave all outputs untouched.
  *
  * Tile arithmetic (Sec. 4.1, space-time tiles; Sec. 3.1 / Appendix D, tile-order flattening)
@@ -156,7 +159,8 @@ int compact_attn_layout_pairs(const ca_layout* layout, const int32_t** pairs, in
                               const int64_t** walk_ptr, const int32_t** walk);
 
 /* Copy the layout's device-side tables (CSR, order, padding masks) to the current HIP device.
- * Synchronous; idempotent.  The compute calls below do it on first use if it was not called.
+ * Synchronous; idempotent.  The compute calls below do it on first use if it was not called
+ * (not possible while their stream is being captured).
  * Errors: CA_ERR_ALLOC, CA_ERR_HIP. */
 int compact_attn_layout_upload(ca_layout* layout);
 
@@ -173,7 +177,8 @@ int compact_attn_permute(const void* src, void* dst, ca_layout* layout, int32_t 
 
 /* Sparse attention forward (Appendix D: block-wise pass with online softmax over kept tiles).
  *   q, k, v, out: device pointers, [batch, heads, N_pad, D] in tile order; padding slots of
- *   k and v are ignored, padding rows of out are written as zero.  out must not alias q/k/v.
+ *   k and v are ignored, padding rows of out are written as zero.  out must not overlap q/k/v
+ *   (byte ranges of the whole tensors are compared).
  * For each query tile i of each head:  out_i = softmax(scale * Q_i K_J^T) V_J, J = real tokens of
  * the kept key tiles.  A row whose kept set holds no real key yields zeros.
  * bf16 problems run on the MFMA kernel: bf16 operands, fp32 accumulation and softmax state,

@@ -3,6 +3,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -61,7 +62,79 @@ void free_device_tables(ca::DeviceTables& d) {
   d = ca::DeviceTables{};
 }
 
-int ensure_uploaded(ca_layout* L) {
+// Host images of the tables the kernels read, packed from the layout's host tables.
+struct PackedTables {
+  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk, tile_origin;
+};
+
+// The kernels read one packed word per kept tile: tile id | padding class << 24, and bit 31 set
+// when the upper half of the tile's slots is padding only (such a tile costs half the products).
+// `forward_only` leaves out what only the dense and the natural-order walks read.
+int pack_tables(const ca_layout* L, bool forward_only, PackedTables& t) {
+  if (L->n >= (int64_t)1 << 24 || L->class_mask.size() > 127) {
+    set_error("layout too large for the device tables (%lld tiles, %zu padding classes)", (long long)L->n,
+              L->class_mask.size());
+    return CA_ERR_UNSUPPORTED;
+  }
+  try {
+    std::vector<uint32_t> class_word(L->class_mask.size());
+    const int words = (int)((L->B + 31) / 32);
+    for (size_t c = 0; c < class_word.size(); ++c) {
+      bool upper_empty = words >= 2;
+      for (int w = words / 2; w < words; ++w) upper_empty = upper_empty && L->class_mask[c].w[w] == 0;
+      class_word[c] = ((uint32_t)c << 24) | (upper_empty ? 0x80000000u : 0u);
+    }
+    // two words of padding: the kernels fetch these tables two entries ahead of the one in use
+    t.col_meta.assign(L->col_idx.size() + 2, 0);
+    for (size_t i = 0; i < L->col_idx.size(); ++i)
+      t.col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
+    if (!forward_only) {
+      t.dense_meta.assign(L->n + 2, 0);
+      for (int64_t i = 0; i < L->n; ++i) t.dense_meta[i] = (int32_t)((uint32_t)i | class_word[L->tile_class[i]]);
+      // natural-order row of slot 0 of every tile (kernels that gather tiles from natural order)
+      const ca_problem& pr = L->prob;
+      const int64_t n_video = (int64_t)pr.T * pr.H * pr.W;
+      if (L->N_real < ((int64_t)1 << 31)) {
+        t.tile_origin.resize(L->n);
+        for (int64_t i = 0; i < L->n; ++i) {
+          if (i >= L->n_vid) {
+            t.tile_origin[i] = (int32_t)(n_video + (i - L->n_vid) * L->B);
+          } else {
+            const int64_t kw = i % L->nW, kh = (i / L->nW) % L->nH, kt = i / ((int64_t)L->nW * L->nH);
+            t.tile_origin[i] = (int32_t)(((kt * pr.tt) * pr.H + kh * pr.th) * pr.W + kw * pr.tw);
+          }
+        }
+      }
+    }
+    if (!L->pair_rows.empty()) {
+      // walk words of the paired kernel carry the class in bits 24-29, below the two membership bits
+      if (L->class_mask.size() > 63) {
+        set_error("layout has too many padding classes for the paired kernel (%zu)", L->class_mask.size());
+        return CA_ERR_UNSUPPORTED;
+      }
+      t.pair_walk.assign(L->pair_walk.size() + 2, 0);
+      for (size_t i = 0; i < L->pair_walk.size(); ++i) {
+        const uint32_t w = (uint32_t)L->pair_walk[i];
+        t.pair_walk[i] = (int32_t)(w | ((uint32_t)L->tile_class[w & 0xffffffu] << 24));
+      }
+      if (!forward_only) {
+        t.dense_pair_walk.assign(L->n + 2, 0);
+        for (int64_t i = 0; i < L->n; ++i)
+          t.dense_pair_walk[i] =
+              (int32_t)((uint32_t)i | ((uint32_t)L->tile_class[i] << 24) | ca::kPairInFirst | ca::kPairInSecond);
+      }
+    }
+  } catch (const std::bad_alloc&) {
+    set_error("out of host memory while packing the device tables");
+    return CA_ERR_ALLOC;
+  }
+  return CA_OK;
+}
+
+// Makes sure the layout's tables are on the current device.  The first call for a layout allocates
+// device memory and copies synchronously, which a stream under capture must not see: there the call
+// fails and names compact_attn_layout_upload instead.
+int ensure_uploaded(ca_layout* L, hipStream_t stream) {
   std::lock_guard<std::mutex> lock(L->upload_mutex);
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
@@ -73,74 +146,32 @@ int ensure_uploaded(ca_layout* L) {
     }
     return CA_OK;
   }
-  // The kernels read one packed word per kept tile: tile id | padding class << 24, and bit 31 set
-  // when the upper half of the tile's slots is padding only (such a tile costs half the products).
-  if (L->n >= (int64_t)1 << 24 || L->class_mask.size() > 127) {
-    set_error("layout too large for the device tables (%lld tiles, %zu padding classes)", (long long)L->n,
-              L->class_mask.size());
-    return CA_ERR_UNSUPPORTED;
+  if (stream) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    e = hipStreamIsCapturing(stream, &cap);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
+    if (cap != hipStreamCaptureStatusNone) {
+      set_error("the layout's tables are not on the device yet and the stream is being captured: call "
+                "compact_attn_layout_upload before the capture");
+      return CA_ERR_INVALID_ARG;
+    }
   }
-  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk, tile_origin;
-  try {
-    std::vector<uint32_t> class_word(L->class_mask.size());
-    const int words = (int)((L->B + 31) / 32);
-    for (size_t c = 0; c < class_word.size(); ++c) {
-      bool upper_empty = words >= 2;
-      for (int w = words / 2; w < words; ++w) upper_empty = upper_empty && L->class_mask[c].w[w] == 0;
-      class_word[c] = ((uint32_t)c << 24) | (upper_empty ? 0x80000000u : 0u);
-    }
-    // two words of padding: the kernels fetch these tables two entries ahead of the one in use
-    col_meta.assign(L->col_idx.size() + 2, 0);
-    for (size_t i = 0; i < L->col_idx.size(); ++i)
-      col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
-    dense_meta.assign(L->n + 2, 0);
-    for (int64_t t = 0; t < L->n; ++t) dense_meta[t] = (int32_t)((uint32_t)t | class_word[L->tile_class[t]]);
-    // natural-order row of slot 0 of every tile (kernels that gather tiles from natural order)
-    const ca_problem& pr = L->prob;
-    const int64_t n_video = (int64_t)pr.T * pr.H * pr.W;
-    if (L->N_real < ((int64_t)1 << 31)) {
-      tile_origin.resize(L->n);
-      for (int64_t t = 0; t < L->n; ++t) {
-        if (t >= L->n_vid) {
-          tile_origin[t] = (int32_t)(n_video + (t - L->n_vid) * L->B);
-        } else {
-          const int64_t kw = t % L->nW, kh = (t / L->nW) % L->nH, kt = t / ((int64_t)L->nW * L->nH);
-          tile_origin[t] = (int32_t)(((kt * pr.tt) * pr.H + kh * pr.th) * pr.W + kw * pr.tw);
-        }
-      }
-    }
-    if (!L->pair_rows.empty()) {
-      // walk words of the paired kernel carry the class in bits 24-29, below the two membership bits
-      if (L->class_mask.size() > 63) {
-        set_error("layout has too many padding classes for the paired kernel (%zu)", L->class_mask.size());
-        return CA_ERR_UNSUPPORTED;
-      }
-      pair_walk.assign(L->pair_walk.size() + 2, 0);
-      for (size_t i = 0; i < L->pair_walk.size(); ++i) {
-        const uint32_t w = (uint32_t)L->pair_walk[i];
-        pair_walk[i] = (int32_t)(w | ((uint32_t)L->tile_class[w & 0xffffffu] << 24));
-      }
-      dense_pair_walk.assign(L->n + 2, 0);
-      for (int64_t t = 0; t < L->n; ++t)
-        dense_pair_walk[t] = (int32_t)((uint32_t)t | ((uint32_t)L->tile_class[t] << 24) | ca::kPairInFirst | ca::kPairInSecond);
-    }
-  } catch (const std::bad_alloc&) {
-    set_error("out of host memory while packing the device tables");
-    return CA_ERR_ALLOC;
-  }
+  PackedTables t;
+  int st = pack_tables(L, false, t);
+  if (st != CA_OK) return st;
   ca::DeviceTables d;
-  int st = upload_vec(L->row_ptr.data(), L->row_ptr.size(), &d.row_ptr);
-  if (st == CA_OK) st = upload_vec(col_meta.data(), col_meta.size(), &d.col_meta);
-  if (st == CA_OK) st = upload_vec(dense_meta.data(), dense_meta.size(), &d.dense_meta);
+  st = upload_vec(L->row_ptr.data(), L->row_ptr.size(), &d.row_ptr);
+  if (st == CA_OK) st = upload_vec(t.col_meta.data(), t.col_meta.size(), &d.col_meta);
+  if (st == CA_OK) st = upload_vec(t.dense_meta.data(), t.dense_meta.size(), &d.dense_meta);
   if (st == CA_OK) st = upload_vec(L->order.data(), L->order.size(), &d.order);
   if (st == CA_OK) st = upload_vec(L->pair_rows.data(), L->pair_rows.size(), &d.pair_rows);
   d.num_pairs = (int64_t)L->pair_rows.size() / 2;
   if (st == CA_OK && d.num_pairs) st = upload_vec(L->pair_walk_ptr.data(), L->pair_walk_ptr.size(), &d.pair_walk_ptr);
-  if (st == CA_OK && d.num_pairs) st = upload_vec(pair_walk.data(), pair_walk.size(), &d.pair_walk);
-  if (st == CA_OK && d.num_pairs) st = upload_vec(dense_pair_walk.data(), dense_pair_walk.size(), &d.dense_pair_walk);
+  if (st == CA_OK && d.num_pairs) st = upload_vec(t.pair_walk.data(), t.pair_walk.size(), &d.pair_walk);
+  if (st == CA_OK && d.num_pairs) st = upload_vec(t.dense_pair_walk.data(), t.dense_pair_walk.size(), &d.dense_pair_walk);
   if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
-  if (st == CA_OK && !tile_origin.empty()) st = upload_vec(tile_origin.data(), tile_origin.size(), &d.tile_origin);
+  if (st == CA_OK && !t.tile_origin.empty()) st = upload_vec(t.tile_origin.data(), t.tile_origin.size(), &d.tile_origin);
   if (st != CA_OK) {
     free_device_tables(d);
     return st;
@@ -149,6 +180,12 @@ int ensure_uploaded(ca_layout* L) {
   L->device = dev;
   L->uploaded = true;
   return CA_OK;
+}
+
+// Do the byte ranges [a, a + na) and [b, b + nb) share a byte?
+bool ranges_overlap(const void* a, int64_t na, const void* b, int64_t nb) {
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
 }
 
 int check_attn_support(const ca_layout* L) {
@@ -171,17 +208,18 @@ int check_attn_support(const ca_layout* L) {
   return CA_OK;
 }
 
-int run_attention(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream, bool dense,
-                  bool natural = false) {
-  ca::clear_error();
+// Argument checks shared by the attention entry points.  `natural` selects the natural-order tensor length.
+int check_attention_args(const void* q, const void* k, const void* v, const ca_layout* L, const void* out, bool natural) {
   if (!q || !k || !v || !L || !out) return fail(CA_ERR_INVALID_ARG, "null argument");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
     return fail(CA_ERR_INVALID_ARG, "q, k, v and out must be 16-byte aligned");
-  if (out == q || out == k || out == v) return fail(CA_ERR_INVALID_ARG, "out must not alias q, k or v");
   int st = check_attn_support(L);
   if (st != CA_OK) return st;
+  const ca_problem& p = L->prob;
+  const int64_t bytes = (int64_t)p.batch * p.num_heads * (natural ? L->N_real : L->N_pad) * p.head_dim * elem_size(p.dtype);
+  if (ranges_overlap(out, bytes, q, bytes) || ranges_overlap(out, bytes, k, bytes) || ranges_overlap(out, bytes, v, bytes))
+    return fail(CA_ERR_INVALID_ARG, "out must not overlap q, k or v");
   if (natural) {
-    const ca_problem& p = L->prob;
     if (p.dtype != CA_BF16) return fail(CA_ERR_UNSUPPORTED, "natural-order attention is built for bf16 problems only");
     const int rows_per_block = 1024 / (p.head_dim * 2);
     if (p.tw % rows_per_block != 0) {
@@ -191,22 +229,26 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
     }
     if (L->N_real >= ((int64_t)1 << 31)) return fail(CA_ERR_UNSUPPORTED, "natural-order attention needs fewer than 2^31 tokens");
   }
-  st = ensure_uploaded(L);
-  if (st != CA_OK) return st;
+  return CA_OK;
+}
+
+// Fills the kernel arguments from the problem and a set of device tables, and launches.
+int launch_attention(const void* q, const void* k, const void* v, const ca_layout* L, const ca::DeviceTables& t, void* out,
+                     void* stream, bool dense, bool natural) {
   ca::AttnArgs a{};
   a.q = q;
   a.k = k;
   a.v = v;
   a.out = out;
-  a.row_ptr = dense ? nullptr : L->dev.row_ptr;
-  a.col_meta = dense ? L->dev.dense_meta : L->dev.col_meta;
-  a.order = dense ? nullptr : L->dev.order;
-  a.pair_rows = L->dev.pair_rows;
-  a.num_pairs = L->dev.num_pairs;
-  a.pair_walk_ptr = dense ? nullptr : L->dev.pair_walk_ptr;
-  a.pair_walk = dense ? L->dev.dense_pair_walk : L->dev.pair_walk;
-  a.tile_class = L->dev.tile_class;
-  a.class_mask = L->dev.class_mask;
+  a.row_ptr = dense ? nullptr : t.row_ptr;
+  a.col_meta = dense ? t.dense_meta : t.col_meta;
+  a.order = dense ? nullptr : t.order;
+  a.pair_rows = t.pair_rows;
+  a.num_pairs = t.num_pairs;
+  a.pair_walk_ptr = dense ? nullptr : t.pair_walk_ptr;
+  a.pair_walk = dense ? t.dense_pair_walk : t.pair_walk;
+  a.tile_class = t.tile_class;
+  a.class_mask = t.class_mask;
   a.batch = L->prob.batch;
   a.num_heads = L->prob.num_heads;
   a.n = L->n;
@@ -214,7 +256,7 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   a.D = L->prob.head_dim;
   a.scale = L->scale;
   a.natural = natural ? 1 : 0;
-  a.tile_origin = L->dev.tile_origin;
+  a.tile_origin = t.tile_origin;
   a.H = L->prob.H;
   a.W = L->prob.W;
   a.th = L->prob.th;
@@ -225,6 +267,16 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
                                                 : ca::launch_attn_f32(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, dense ? "dense attention launch" : "sparse attention launch");
   return CA_OK;
+}
+
+int run_attention(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream, bool dense,
+                  bool natural = false) {
+  ca::clear_error();
+  int st = check_attention_args(q, k, v, L, out, natural);
+  if (st != CA_OK) return st;
+  st = ensure_uploaded(L, (hipStream_t)stream);
+  if (st != CA_OK) return st;
+  return launch_attention(q, k, v, L, L->dev, out, stream, dense, natural);
 }
 
 // Checks a problem description and allocates a layout with its geometry filled in (no tables yet).
@@ -373,7 +425,7 @@ int compact_attn_layout_pairs(const ca_layout* L, const int32_t** pairs, int64_t
 int compact_attn_layout_upload(ca_layout* L) {
   ca::clear_error();
   if (!L) return fail(CA_ERR_INVALID_ARG, "null layout");
-  return ensure_uploaded(L);
+  return ensure_uploaded(L, nullptr);
 }
 
 void compact_attn_free_layout(ca_layout* L) {
@@ -386,9 +438,14 @@ int compact_attn_permute(const void* src, void* dst, ca_layout* L, int32_t inver
   ca::clear_error();
   if (!src || !dst || !L) return fail(CA_ERR_INVALID_ARG, "null argument");
   if (!aligned16(src) || !aligned16(dst)) return fail(CA_ERR_INVALID_ARG, "src and dst must be 16-byte aligned");
-  if (src == dst) return fail(CA_ERR_INVALID_ARG, "src and dst must not overlap");
   if (inverse != 0 && inverse != 1) return fail(CA_ERR_INVALID_ARG, "inverse must be 0 or 1");
   const ca_problem& p = L->prob;
+  {
+    const int64_t per_token = (int64_t)p.batch * p.num_heads * p.head_dim * elem_size(p.dtype);
+    const int64_t natural_bytes = per_token * L->N_real, tiled_bytes = per_token * L->N_pad;
+    if (ranges_overlap(src, inverse ? tiled_bytes : natural_bytes, dst, inverse ? natural_bytes : tiled_bytes))
+      return fail(CA_ERR_INVALID_ARG, "src and dst must not overlap");
+  }
   ca::PermuteArgs a{};
   a.src = src;
   a.dst = dst;
@@ -430,7 +487,12 @@ int compact_attn_tile_mass(const void* q, const void* k, ca_layout* L, float* ma
               (long long)L->B, p.head_dim);
     return CA_ERR_UNSUPPORTED;
   }
-  const int st = ensure_uploaded(L);
+  const int64_t in_bytes = (int64_t)p.batch * p.num_heads * L->N_pad * p.head_dim * 2;
+  const int64_t mass_bytes = (int64_t)p.batch * p.num_heads * L->n * L->n * 4;
+  if ((reinterpret_cast<uintptr_t>(mass) & 3u) != 0) return fail(CA_ERR_INVALID_ARG, "mass must be 4-byte aligned");
+  if (ranges_overlap(mass, mass_bytes, q, in_bytes) || ranges_overlap(mass, mass_bytes, k, in_bytes))
+    return fail(CA_ERR_INVALID_ARG, "mass must not overlap q or k");
+  const int st = ensure_uploaded(L, (hipStream_t)stream);
   if (st != CA_OK) return st;
   ca::MassArgs a{};
   a.q = q;

@@ -1,5 +1,5 @@
 // Internal representation of a built layout.  Host tables are filled by layout.cpp (no HIP
-// calls); device copies are created by upload.cpp and consumed by the kernels.
+// calls); device copies are created by api.cpp and consumed by the kernels.
 #pragma once
 
 #include <cstdint>

@@ -157,7 +157,29 @@ def test_unsupported_shapes_rejected_before_any_device_work():
     assert st_ == binding.CA_ERR_UNSUPPORTED
     assert "bf16" in ca.compact_attn_last_error()
     assert lib.compact_attn_forward(addr + 1, addr + 16, addr + 32, lay.handle, addr, None) == binding.CA_ERR_INVALID_ARG
-    assert lib.compact_attn_forward(addr, addr + 16, addr + 32, lay.handle, addr, None) == binding.CA_ERR_INVALID_ARG
+
+
+def test_overlapping_buffers_rejected_on_the_host():
+    """Byte ranges of the whole tensors are compared, not base pointers: an output that starts inside
+    an input is refused before anything is enqueued (the addresses below are never dereferenced)."""
+    lay = ca.compact_attn_build_layout(2, 8, 8, (1, 8, 8), 0, 1, 2, 64, "bf16", [[(0, (0, 0), ABSENT)]] * 2)
+    lib = ca.load_library()
+    size = 2 * lay.n_tokens_padded * 64 * 2                   # bytes of one tile-ordered tensor
+    base = 1 << 30
+    q, k, v = base, base + size, base + 2 * size
+    for fn in (lib.compact_attn_forward, lib.compact_attn_dense):
+        for out in (q, q + 16, k + size - 16, v - 16, v + size - 16):
+            assert fn(q, k, v, lay.handle, out, None) == binding.CA_ERR_INVALID_ARG
+            assert "overlap" in ca.compact_attn_last_error()
+    nat = 2 * lay.n_tokens_real * 64 * 2
+    assert lib.compact_attn_forward_natural(q, k, v, lay.handle, q + nat - 16, None) == binding.CA_ERR_INVALID_ARG
+    assert lib.compact_attn_permute(q, q + 16, lay.handle, 0, None) == binding.CA_ERR_INVALID_ARG
+    assert lib.compact_attn_permute(q, q + size - 16, lay.handle, 1, None) == binding.CA_ERR_INVALID_ARG
+    mass_bytes = 2 * lay.n_tiles * lay.n_tiles * 4
+    assert lib.compact_attn_tile_mass(q, k, lay.handle, k - mass_bytes + 4, None) == binding.CA_ERR_INVALID_ARG
+    assert "overlap" in ca.compact_attn_last_error()
+    assert lib.compact_attn_tile_mass(q, k, lay.handle, base - mass_bytes - 2, None) == binding.CA_ERR_INVALID_ARG
+    assert "aligned" in ca.compact_attn_last_error()
 
 
 # ---------------------------------------------------------------- import, union, similarity
