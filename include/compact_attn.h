@@ -188,6 +188,24 @@ int compact_attn_permute(const void* src, void* dst, ca_layout* layout, int32_t 
 int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
                          void* stream);
 
+/* compact_attn_forward for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result, bit for bit, but the layout's tables (row offsets, packed tile words, launch order, padding
+ * masks, pair walks) are read from a fixed 8 MiB device array inside the library instead of from
+ * memory allocated at compact_attn_layout_upload; the call makes no hipMalloc / hipFree and needs no
+ * prior upload.  Every GPU the library runs on holds one such array until the process ends.
+ *   - A layout whose tables exceed the array (about 1.9 million kept tile pairs) is rejected with
+ *     CA_ERR_UNSUPPORTED and a message that states both sizes; nothing is enqueued.
+ *   - The array keeps the tables of the layout the previous call on this GPU used.  A call with the
+ *     same layout enqueues the kernel only; a call with another layout first enqueues one
+ *     host-to-device copy of that layout's tables on `stream` (the layout must stay alive until that
+ *     copy has run).  Such a copy cannot be recorded into a capturing stream: make one call with
+ *     the layout before the capture, otherwise CA_ERR_INVALID_ARG.
+ *   - All calls on one GPU share the array: calls that may overlap in time on different streams
+ *     race and must be ordered by the caller. */
+int compact_attn_forward_static(const void* q, const void* k, const void* v, ca_layout* layout, void* out,
+                                void* stream);
+
 /* The same forward on tensors in NATURAL token order (Sec. 3.1's tile-wise flattening and its inverse
  * folded into the attention pass: the kernel gathers the K/V tiles and the Q rows from natural
  * order and scatters the output rows back, so no compact_attn_permute pass is needed).

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     compact_attn_dense,
     compact_attn_forward,
     compact_attn_forward_natural,
+    compact_attn_forward_static,
     compact_attn_free_layout,
     compact_attn_last_error,
     compact_attn_layout_csr,

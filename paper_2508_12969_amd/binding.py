@@ -35,6 +35,7 @@ EXPORTED = (
     "compact_attn_free_layout",
     "compact_attn_permute",
     "compact_attn_forward",
+    "compact_attn_forward_static",
     "compact_attn_forward_natural",
     "compact_attn_dense",
     "compact_attn_tile_mass",
@@ -107,6 +108,7 @@ def load_library():
     lib.compact_attn_permute.argtypes = [vp, vp, vp, i32, vp]
     lib.compact_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_forward_natural.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.compact_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_dense.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.compact_attn_tile_mass.argtypes = [vp, vp, vp, vp, vp]
     lib.compact_attn_search_head.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32), i32, ctypes.c_double,
@@ -307,6 +309,12 @@ def _attention(fn, q, k, v, layout, out, stream, padded=True):
 def compact_attn_forward(q, k, v, layout, out=None, stream=None):
     """Sparse attention over tile-ordered, padded q/k/v [batch, heads, N_pad, D]."""
     return _attention(load_library().compact_attn_forward, q, k, v, layout, out, stream)
+
+
+def compact_attn_forward_static(q, k, v, layout, out=None, stream=None):
+    """compact_attn_forward with the layout tables in the library's fixed device array (no allocation
+    inside the call; pass `out`, or the binding allocates it before the call)."""
+    return _attention(load_library().compact_attn_forward_static, q, k, v, layout, out, stream)
 
 
 def compact_attn_forward_natural(q, k, v, layout, out=None, stream=None):

@@ -1,6 +1,7 @@
 // C-ABI entry points: argument checking, layout life cycle, device upload, kernel dispatch.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -13,6 +14,22 @@
 using ca::set_error;
 
 namespace {
+
+// Device memory of compact_attn_forward_static: the layout tables of the sparse forward live here
+// instead of in allocated memory.  Every GPU the library runs on holds its own copy of the array
+// until the process ends.  In host code the name below is only a handle for hipGetSymbolAddress;
+// the address kernels and copies use is the per-device pointer kept in g_scratch.
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+struct ScratchState {
+  unsigned char* ptr = nullptr;  // device address of `scratch` on this device
+  uint64_t owner = 0;            // serial of the layout whose tables the last call enqueued there
+};
+ScratchState g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+std::atomic<uint64_t> g_next_serial{1};
 
 int fail(int status, const char* what) {
   set_error("%s", what);
@@ -279,6 +296,47 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
   return launch_attention(q, k, v, L, L->dev, out, stream, dense, natural);
 }
 
+// Packs the sparse forward's tables into L->static_image (once per layout).  Caller holds g_scratch_mutex.
+int build_static_image(ca_layout* L) {
+  if (!L->static_image.empty()) return CA_OK;
+  PackedTables t;
+  int st = pack_tables(L, true, t);
+  if (st != CA_OK) return st;
+  auto aligned = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  struct Part {
+    const void* src;
+    size_t bytes;
+    size_t* off;
+  };
+  ca_layout::StaticOffsets& o = L->static_off;
+  const bool paired = !L->pair_rows.empty();
+  const Part parts[] = {
+      {L->row_ptr.data(), L->row_ptr.size() * sizeof(int64_t), &o.row_ptr},
+      {t.col_meta.data(), t.col_meta.size() * sizeof(int32_t), &o.col_meta},
+      {L->order.data(), L->order.size() * sizeof(int32_t), &o.order},
+      {L->pair_rows.data(), paired ? L->pair_rows.size() * sizeof(int32_t) : 0, &o.pair_rows},
+      {L->pair_walk_ptr.data(), paired ? L->pair_walk_ptr.size() * sizeof(int64_t) : 0, &o.pair_walk_ptr},
+      {t.pair_walk.data(), paired ? t.pair_walk.size() * sizeof(int32_t) : 0, &o.pair_walk},
+      {L->tile_class.data(), L->tile_class.size() * sizeof(int32_t), &o.tile_class},
+      {L->class_mask.data(), L->class_mask.size() * sizeof(ca::SlotMask), &o.class_mask},
+  };
+  size_t total = 0;
+  for (const Part& p : parts) {
+    *p.off = total;
+    total += aligned(p.bytes);
+  }
+  if (total == 0) total = 256;
+  try {
+    L->static_image.assign(total, 0);
+  } catch (const std::bad_alloc&) {
+    set_error("out of host memory while packing the device tables");
+    return CA_ERR_ALLOC;
+  }
+  for (const Part& p : parts)
+    if (p.bytes) std::memcpy(L->static_image.data() + *p.off, p.src, p.bytes);
+  return CA_OK;
+}
+
 // Checks a problem description and allocates a layout with its geometry filled in (no tables yet).
 int new_layout(const ca_problem& p, ca_layout** out) {
   if (p.T <= 0 || p.H <= 0 || p.W <= 0) return fail(CA_ERR_INVALID_ARG, "T, H, W must be positive");
@@ -299,6 +357,7 @@ int new_layout(const ca_problem& p, ca_layout** out) {
 
   ca_layout* L = new (std::nothrow) ca_layout();
   if (!L) return fail(CA_ERR_ALLOC, "out of host memory");
+  L->serial = g_next_serial.fetch_add(1);
   L->prob = p;
   L->nT = (int32_t)nT;
   L->nH = (int32_t)nH;
@@ -467,6 +526,66 @@ int compact_attn_permute(const void* src, void* dst, ca_layout* L, int32_t inver
 
 int compact_attn_forward(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {
   return run_attention(q, k, v, L, out, stream, false);
+}
+
+int compact_attn_forward_static(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {
+  ca::clear_error();
+  int st = check_attention_args(q, k, v, L, out, false);
+  if (st != CA_OK) return st;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(CA_ERR_UNSUPPORTED, "device index beyond the static table slots");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  ScratchState& sc = g_scratch[dev];
+  if (!sc.ptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress of the static table array");
+    sc.ptr = static_cast<unsigned char*>(p);
+  }
+  st = build_static_image(L);
+  if (st != CA_OK) return st;
+  if (L->static_image.size() > kScratchBytes) {
+    set_error("the layout's tables take %zu bytes, the static device array holds %zu: use compact_attn_forward",
+              L->static_image.size(), kScratchBytes);
+    return CA_ERR_UNSUPPORTED;
+  }
+  if (sc.owner != L->serial) {
+    // the array holds another layout's tables (or nothing yet): replace them, in stream order
+    if (stream) {
+      hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+      e = hipStreamIsCapturing((hipStream_t)stream, &cap);
+      if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
+      if (cap != hipStreamCaptureStatusNone) {
+        set_error("the static device array does not hold this layout's tables and the stream is being captured: "
+                  "make one call with this layout before the capture");
+        return CA_ERR_INVALID_ARG;
+      }
+    }
+    e = hipMemcpyAsync(sc.ptr, L->static_image.data(), L->static_image.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) {
+      sc.owner = 0;
+      return hip_fail(e, "copy of the layout tables into the static device array");
+    }
+    sc.owner = L->serial;
+  }
+  const ca_layout::StaticOffsets& o = L->static_off;
+  ca::DeviceTables t;
+  t.row_ptr = reinterpret_cast<int64_t*>(sc.ptr + o.row_ptr);
+  t.col_meta = reinterpret_cast<int32_t*>(sc.ptr + o.col_meta);
+  t.order = reinterpret_cast<int32_t*>(sc.ptr + o.order);
+  t.num_pairs = (int64_t)L->pair_rows.size() / 2;
+  if (t.num_pairs) {
+    t.pair_rows = reinterpret_cast<int32_t*>(sc.ptr + o.pair_rows);
+    t.pair_walk_ptr = reinterpret_cast<int64_t*>(sc.ptr + o.pair_walk_ptr);
+    t.pair_walk = reinterpret_cast<int32_t*>(sc.ptr + o.pair_walk);
+  }
+  t.tile_class = reinterpret_cast<int32_t*>(sc.ptr + o.tile_class);
+  t.class_mask = reinterpret_cast<ca::SlotMask*>(sc.ptr + o.class_mask);
+  st = launch_attention(q, k, v, L, t, out, stream, false, false);
+  if (st != CA_OK) sc.owner = 0;
+  return st;
 }
 
 int compact_attn_forward_natural(const void* q, const void* k, const void* v, ca_layout* L, void* out, void* stream) {

@@ -58,6 +58,15 @@ struct ca_layout {
   bool uploaded = false;
   int device = -1;
   ca::DeviceTables dev;
+
+  // The tables of the sparse forward as one block of bytes with 256-byte aligned parts, ready to be
+  // copied into a fixed device array (compact_attn_forward_static); packed on first use.
+  uint64_t serial = 0;                      // unique per layout object, never reused
+  std::vector<unsigned char> static_image;
+  struct StaticOffsets {
+    size_t row_ptr = 0, col_meta = 0, order = 0, pair_rows = 0, pair_walk_ptr = 0, pair_walk = 0, tile_class = 0,
+           class_mask = 0;
+  } static_off;
 };
 
 namespace ca {

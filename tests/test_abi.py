@@ -167,7 +167,7 @@ def test_overlapping_buffers_rejected_on_the_host():
     size = 2 * lay.n_tokens_padded * 64 * 2                   # bytes of one tile-ordered tensor
     base = 1 << 30
     q, k, v = base, base + size, base + 2 * size
-    for fn in (lib.compact_attn_forward, lib.compact_attn_dense):
+    for fn in (lib.compact_attn_forward, lib.compact_attn_dense, lib.compact_attn_forward_static):
         for out in (q, q + 16, k + size - 16, v - 16, v + size - 16):
             assert fn(q, k, v, lay.handle, out, None) == binding.CA_ERR_INVALID_ARG
             assert "overlap" in ca.compact_attn_last_error()
