@@ -1,5 +1,8 @@
 // Pieces shared by the bf16 MFMA attention kernels: vector types, the LDS chunk swizzles, the
-// asynchronous global -> LDS tile copy and the partner-lane exchange.
+// asynchronous global -> LDS tile copy (tile order and natural order), the partner-lane exchange,
+// and the tile step itself: what one wave of 32 queries does with one key tile (S^T = K Q^T,
+// padding mask, online softmax with a lazy exponent reference, O^T += V^T P^T) and its epilogue.
+// The kernels differ only in how rows are mapped to workgroups and how the tile list is walked.
 #pragma once
 
 #include "kernels.h"
@@ -23,10 +26,12 @@ constexpr float kMinusInf = -__builtin_inff();
 constexpr float kLazyLog2 = 8.0f;          // the exponent reference may lag the row max by 2^8
 constexpr int kXcdChunk = 32;              // consecutive launch-order entries handed to one XCD
 
-template <int B_, int D_>
+// kWaves_: waves of a workgroup that share the tile copies (B / 32 when a workgroup owns one query
+// tile, twice that when it owns two).
+template <int B_, int D_, int kWaves_ = B_ / 32>
 struct Shape {
   static constexpr int B = B_, D = D_;
-  static constexpr int kWaves = B / 32;           // one wave per 32 queries
+  static constexpr int kWaves = kWaves_;
   static constexpr int kThreads = kWaves * 64;
   static constexpr int kKeyBlocks = B / 32;       // 32-key blocks of a key tile
   static constexpr int kQkSteps = D / 16;         // contraction steps of S^T = K Q^T
@@ -151,6 +156,267 @@ __device__ __forceinline__ float sum_with_partner(float x) {
 #define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 #define WAIT_LGKMCNT0() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
 #define BARRIER() asm volatile("s_barrier" ::: "memory")
+
+typedef __attribute__((address_space(3))) const char* LdsTile;
+
+// Where a wave's share of a key tile comes from.  Tile order: the tile is one contiguous block.
+// Natural order (kNat): a KiB block of a tile (kRowsPerLoad consecutive slots, inside one run of tw
+// tokens) is contiguous there too, at row tile_origin[tile] + (dt*H + dy)*W + dx of the plane; a
+// text tile is contiguous as a whole.  row_in_tile[i] is that offset for the i-th block this wave
+// copies.
+template <class S, bool kNat>
+struct TileSource {
+  int32_t row_in_tile[kNat ? S::kLoadsPerThread : 1];
+  int32_t n_vid, N_real;
+  int wave, lane;
+
+  __device__ __forceinline__ TileSource(const AttnArgs& a, int wave_, int lane_) : wave(wave_), lane(lane_) {
+    n_vid = (int32_t)a.n_vid;
+    N_real = (int32_t)a.N_real;
+    row_in_tile[0] = 0;
+    if constexpr (kNat) {
+#pragma unroll
+      for (int i = 0; i < S::kLoadsPerThread; ++i) {
+        const int slot0 = (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad;
+        const int dx = slot0 % a.tw, run = slot0 / a.tw, dy = run % a.th, dt = run / a.th;
+        row_in_tile[i] = (dt * a.H + dy) * a.W + dx;
+      }
+    }
+  }
+
+  // base: the (batch, head) plane of K or V; origin: tile_origin[tile] (natural order only)
+  template <class Loader>
+  __device__ __forceinline__ void issue(const Loader& loader, const char* base, int tile, int32_t origin, uint32_t lds_addr) const {
+    if constexpr (!kNat) {
+      loader.issue(base + (int64_t)tile * S::kTileBytes, lds_addr, wave);
+    } else {
+      const bool text = tile >= n_vid;
+      const char* sb[S::kLoadsPerThread];
+      bool inside = true;
+#pragma unroll
+      for (int i = 0; i < S::kLoadsPerThread; ++i) {
+        const int32_t row = origin + (text ? (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad : row_in_tile[i]);
+        inside = inside && row + S::kRowsPerLoad <= N_real;
+        sb[i] = base + (int64_t)row * S::kRowBytes;
+      }
+      if (inside) {
+        loader.issue_blocks(sb, lds_addr, wave);
+      } else {
+        // slots past the last token (padding of the last tiles): every lane is pointed at a row of the
+        // tensor; what it fetches is never attended
+#pragma unroll
+        for (int i = 0; i < S::kLoadsPerThread; ++i) {
+          const int32_t row = origin + (text ? (wave * S::kLoadsPerThread + i) * S::kRowsPerLoad : row_in_tile[i]);
+          const int32_t first = min(row, N_real - 1);
+          loader.issue_clamped(base + (int64_t)first * S::kRowBytes, N_real - 1 - first, i, lds_addr, wave, lane);
+        }
+      }
+    }
+  }
+
+  // Natural-order row of slot `slot` of query tile `q_tile` (clamped into the tensor for a padding
+  // slot, whose result is never stored).
+  __device__ __forceinline__ int64_t query_row(const AttnArgs& a, int64_t q_tile, int slot) const {
+    const int dx = slot % a.tw, run = slot / a.tw, dy = run % a.th, dt = run / a.th;
+    const int64_t row = CONST_PTR(int32_t, a.tile_origin)[q_tile] + (q_tile >= a.n_vid ? slot : (dt * a.H + dy) * a.W + dx);
+    return row < a.N_real ? row : a.N_real - 1;
+  }
+};
+
+// One wave's 32 queries: operand fragments, accumulators and softmax state, and the tile step.
+//
+// Transposed formulation.  Scores are computed as S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so in
+// the accumulator a lane holds ONE query (column lane%32) and 16 of the 32 keys of a block; its
+// partner lane^32 holds the other 16.  Row max and row sum are register-local except for a single
+// exchange with the partner lane, and the running max / sum / rescale factor are one scalar per
+// lane.  The output is accumulated transposed as well, O^T = V^T P^T, whose B operand (P^T: keys
+// along the contraction, queries across lanes) is exactly the bf16-rounded score accumulator,
+// register for register: no shuffle and no LDS round trip between the two matrix products.  The
+// contraction order over keys inside a 32-key block is permuted (a lane group owns keys {0-3,
+// 8-11, 16-19, 24-27} + 4*group), and the V^T operand is fetched with the same permutation.
+template <class S>
+struct QueryWave {
+  static constexpr int D = S::D;
+  bf16x8 qf[S::kQkSteps];      // B operand of S^T: lane (qi, g) holds d = 16*step + 8*g .. +7 of its query
+  floatx16 acc_o[S::kDBlocks];
+  // Exponent reference of this lane's query (raw score units): the first tile's row maximum,
+  // afterwards a lagging running maximum.  neg_m holds -m_run in all 16 registers and is the C
+  // operand of the first contraction step, so the score accumulator comes out as (score - reference).
+  floatx16 neg_m;
+  float m_run, l_run;          // l_run: this lane's share of the running sum (partner lane holds the rest)
+  float c2, lazy_raw;          // scale * log2(e); kLazyLog2 in raw score units
+  int qi, g;
+  // per-lane LDS read offsets
+  int k_lane_row_off, k_lane_swz;                              // K: row (32*kb + qi), logical chunk 2*step + g
+  int v_lane_row, v_lane_swz, v_lane_chunk, v_lane_half;       // V: transposing read, see pv()
+
+  __device__ __forceinline__ QueryWave(int lane, float scale) {
+    qi = lane & 31;
+    g = lane >> 5;
+    c2 = scale * kLog2e;
+    lazy_raw = kLazyLog2 / c2;
+    m_run = 0.f;
+    l_run = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
+#pragma unroll
+    for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_o[db][r] = 0.f;
+    k_lane_row_off = qi * S::kRowBytes;
+    k_lane_swz = k_swizzle<D>(qi);  // 32*kb does not change the swizzle
+    // V: lane covers key row 4*g + (lane%16)/4 (+ 32*kb + 16*t + 8*half) and the 8-byte half-chunk
+    // that holds d = 32*db + 16*((lane/16)%2) + 4*(lane%4) .. +3
+    v_lane_row = 4 * g + ((lane & 15) >> 2);
+    v_lane_swz = v_swizzle<D>(v_lane_row);  // multiples of 8 rows keep it
+    v_lane_chunk = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+    v_lane_half = (lane & 1) * 8;
+  }
+
+  // q_row_ptr: this lane's query row in global memory
+  __device__ __forceinline__ void load_q(const char* q_row_ptr) {
+    const char* Qp = q_row_ptr + g * 16;
+#pragma unroll
+    for (int s = 0; s < S::kQkSteps; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qp + s * 32);
+    // Touch the fragments so that the compiler waits for these loads here, before the loop: inside
+    // the loop the vector-memory counter must belong to the tile copies alone.
+#pragma unroll
+    for (int s = 0; s < S::kQkSteps; ++s) asm volatile("" : "+v"(qf[s]));
+  }
+
+  // ---- S^T = K Q^T for the key blocks [kKb0, kKb1) of the tile in lds_k ------------------------
+  template <int kKb0, int kKb1>
+  __device__ __forceinline__ void qk(LdsTile lds_k, floatx16 (&acc_s)[S::kKeyBlocks]) const {
+#pragma unroll
+    for (int s = 0; s < S::kQkSteps; ++s) {
+#pragma unroll
+      for (int kb = kKb0; kb < kKb1; ++kb) {
+        const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
+        const bf16x8 kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(lds_k + off);
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- padding keys never take part ------------------------------------------------------------
+  // Only tiles on a padded face of the grid have invalid slots (cls != 0, wave-uniform).  The valid
+  // bits of a 32-key block are one scalar word; the select mask of each score register is built on
+  // the scalar unit (lanes 0-31 hold key 8*(r/4) + r%4 of the block, lanes 32-63 that key + 4) and
+  // applied with one v_cndmask per register.
+  template <class MaskPtr>
+  __device__ __forceinline__ void mask_padding_keys(floatx16 (&acc_s)[S::kKeyBlocks], int cls, MaskPtr class_mask) const {
+    if (cls == 0) return;
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
+      const uint32_t bits = class_mask[cls * 4 + kb];
+      if (bits != 0xffffffffu) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int bit = 8 * (r / 4) + (r % 4);
+          const uint32_t lo = 0u - ((bits >> bit) & 1u), hi = 0u - ((bits >> (bit + 4)) & 1u);
+          const uint64_t keep = (uint64_t)lo | ((uint64_t)hi << 32);
+          asm("v_cndmask_b32 %0, %1, %0, %2" : "+v"(acc_s[kb][r]) : "v"(kMinusInf), "s"(keep));
+        }
+      }
+    }
+  }
+
+  // ---- online softmax (one query per lane) -------------------------------------------------------
+  // acc_s holds score - reference in raw units.  The reference is set to the row maximum on the
+  // first tile of the row (`first`, wave-uniform) and afterwards moves only for rows whose maximum
+  // exceeds it by more than 2^kLazyLog2 (probabilities then stay below that factor, far inside fp32
+  // and bf16 range); the accumulator rescale O *= alpha is then a rarely taken wave-uniform branch
+  // and the common path is exp2 alone.  The result is still the exact softmax: numerator and
+  // denominator share the same reference.  Probabilities are rounded to bf16 (the B operand of the
+  // second product); the row sum adds up the rounded values, two per v_dot2, so numerator and
+  // denominator see the same numbers.
+  __device__ __forceinline__ void softmax(floatx16 (&acc_s)[S::kKeyBlocks], bool first, bf16x8 (&pf)[S::kKeyBlocks][2]) {
+    float mx = acc_s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
+    mx = max_with_partner(mx);
+    {
+      const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
+      if (first || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
+        float delta = (first || mx > lazy_raw) ? mx : 0.f;
+        if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
+        const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
+        m_run += delta;
+        l_run *= alpha;
+#pragma unroll
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
+#pragma unroll
+        for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
+      }
+    }
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
+#pragma unroll
+    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        bf16x8 p8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(acc_s[kb][8 * t + e] * c2);
+        pf[kb][t] = p8;
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 0, 1), ones, l_run, false);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 2, 3), ones, l_run, false);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 4, 5), ones, l_run, false);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 6, 7), ones, l_run, false);
+      }
+  }
+
+  // ---- O^T += V^T P^T for the key blocks [kKb0, kKb1) of the tile in lds_v ----------------------
+  // V stays row-major [key][d] in LDS and is read with ds_read_b64_tr_b16, which hands each lane
+  // four consecutive keys of one d column, i.e. the A operand of O^T.
+  template <int kKb0, int kKb1>
+  __device__ __forceinline__ void pv(LdsTile lds_v, const bf16x8 (&pf)[S::kKeyBlocks][2]) {
+#pragma unroll
+    for (int kb = kKb0; kb < kKb1; ++kb) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int db = 0; db < S::kDBlocks; ++db) {
+          const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
+          const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
+          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(lds_v + base));
+          const shortx4 hi =
+              __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(lds_v + base + 8 * S::kRowBytes));
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], acc_o[db], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- epilogue: O = O^T / l; a padding query (q_real false) and an empty row give zeros ---------
+  // out_row: this lane's output row in global memory; `write` false: the layout has no row for this
+  // lane's slot (a padding slot in natural order) and nothing is stored
+  __device__ __forceinline__ void store(char* out_row, bool q_real, bool write) const {
+    const float l_tot = sum_with_partner(l_run);
+    const float inv = (q_real && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
+    if (!write) return;
+#pragma unroll
+    for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc_o[db][4 * r4 + e] * inv);
+        const int d0 = db * 32 + 8 * r4 + 4 * g;
+        *reinterpret_cast<bf16x4*>(out_row + d0 * 2) = o4;
+      }
+  }
+};
 
 }  // namespace
 }  // namespace ca
