@@ -75,6 +75,7 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.dense_pair_walk) (void)hipFree(d.dense_pair_walk);
   if (d.tile_class) (void)hipFree(d.tile_class);
   if (d.class_mask) (void)hipFree(d.class_mask);
+  if (d.class_perm) (void)hipFree(d.class_perm);
   if (d.tile_origin) (void)hipFree(d.tile_origin);
   d = ca::DeviceTables{};
 }
@@ -82,6 +83,7 @@ void free_device_tables(ca::DeviceTables& d) {
 // Host images of the tables the kernels read, packed from the layout's host tables.
 struct PackedTables {
   std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk, tile_origin;
+  std::vector<uint8_t> class_perm;
 };
 
 // The kernels read one packed word per kept tile: tile id | padding class << 24, and bit 31 set
@@ -100,6 +102,17 @@ int pack_tables(const ca_layout* L, bool forward_only, PackedTables& t) {
       bool upper_empty = words >= 2;
       for (int w = words / 2; w < words; ++w) upper_empty = upper_empty && L->class_mask[c].w[w] == 0;
       class_word[c] = ((uint32_t)c << 24) | (upper_empty ? 0x80000000u : 0u);
+    }
+    // Query slots of a tile in the order the bf16 kernels hand them to lanes: the slots that hold a
+    // token first, so that the queries of a padded tile fill as few 32-query waves as possible.
+    t.class_perm.assign(L->class_mask.size() * 128, 0);
+    for (size_t c = 0; c < L->class_mask.size(); ++c) {
+      int at = 0;
+      for (int pass = 0; pass < 2; ++pass)
+        for (int slot = 0; slot < (int)L->B && slot < 128; ++slot) {
+          const bool valid = (L->class_mask[c].w[slot >> 5] >> (slot & 31)) & 1u;
+          if (valid == (pass == 0)) t.class_perm[c * 128 + at++] = (uint8_t)slot;
+        }
     }
     // two words of padding: the kernels fetch these tables two entries ahead of the one in use
     t.col_meta.assign(L->col_idx.size() + 2, 0);
@@ -188,6 +201,7 @@ int ensure_uploaded(ca_layout* L, hipStream_t stream) {
   if (st == CA_OK && d.num_pairs) st = upload_vec(t.dense_pair_walk.data(), t.dense_pair_walk.size(), &d.dense_pair_walk);
   if (st == CA_OK) st = upload_vec(L->tile_class.data(), L->tile_class.size(), &d.tile_class);
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
+  if (st == CA_OK) st = upload_vec(t.class_perm.data(), t.class_perm.size(), &d.class_perm);
   if (st == CA_OK && !t.tile_origin.empty()) st = upload_vec(t.tile_origin.data(), t.tile_origin.size(), &d.tile_origin);
   if (st != CA_OK) {
     free_device_tables(d);
@@ -266,6 +280,7 @@ int launch_attention(const void* q, const void* k, const void* v, const ca_layou
   a.pair_walk = dense ? t.dense_pair_walk : t.pair_walk;
   a.tile_class = t.tile_class;
   a.class_mask = t.class_mask;
+  a.class_perm = t.class_perm;
   a.batch = L->prob.batch;
   a.num_heads = L->prob.num_heads;
   a.n = L->n;
@@ -319,6 +334,7 @@ int build_static_image(ca_layout* L) {
       {t.pair_walk.data(), paired ? t.pair_walk.size() * sizeof(int32_t) : 0, &o.pair_walk},
       {L->tile_class.data(), L->tile_class.size() * sizeof(int32_t), &o.tile_class},
       {L->class_mask.data(), L->class_mask.size() * sizeof(ca::SlotMask), &o.class_mask},
+      {t.class_perm.data(), t.class_perm.size(), &o.class_perm},
   };
   size_t total = 0;
   for (const Part& p : parts) {
@@ -583,6 +599,7 @@ int compact_attn_forward_static(const void* q, const void* k, const void* v, ca_
   }
   t.tile_class = reinterpret_cast<int32_t*>(sc.ptr + o.tile_class);
   t.class_mask = reinterpret_cast<ca::SlotMask*>(sc.ptr + o.class_mask);
+  t.class_perm = sc.ptr + o.class_perm;
   st = launch_attention(q, k, v, L, t, out, stream, false, false);
   if (st != CA_OK) sc.owner = 0;
   return st;

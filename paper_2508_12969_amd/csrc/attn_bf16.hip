@@ -63,16 +63,13 @@ void attn_bf16_kernel(AttnArgs a) {
   // one packed word per kept tile: tile id | padding class << 24 (a slice of the packed CSR, or the
   // shared 0..n-1 list of the dense walk)
   const auto meta = CONST_PTR(int32_t, a.col_meta + begin);
-  const auto tile_class = CONST_PTR(int32_t, a.tile_class);
   const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
 
-  // A wave whose 32 query slots are all padding (the far half of a tile on a padded grid face)
-  // takes part in the tile copies and barriers only.
-  const uint32_t q_valid = class_mask[tile_class[q_tile] * 4 + wave];  // slots 32*wave .. +31 are this wave's queries
-  const bool wave_active = q_valid != 0;
-
+  // A wave without a real query (see query_slot) takes part in the tile copies and barriers only.
   QueryWave<S> w(lane, a.scale);
-  const int64_t q_row = kNat ? src.query_row(a, q_tile, wave * 32 + w.qi) : q_tile * B + wave * 32 + w.qi;
+  const QuerySlot qs = query_slot<B>(a, q_tile, wave * 32, w.qi);
+  const bool wave_active = qs.wave_active;
+  const int64_t q_row = kNat ? src.query_row(a, q_tile, qs.slot) : q_tile * B + qs.slot;
   w.load_q(static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes);
 
   const TileLoader<S, false> k_loader(wave, lane);
@@ -108,12 +105,11 @@ void attn_bf16_kernel(AttnArgs a) {
     if (j + 1 < count) src.issue(v_loader, Vp, next_tile, next_origin, lds_v_addr);
   }
 
-  constexpr int kLowerBlocks = S::kKeyBlocks / 2;
   for (int j = 0; j < active_count; ++j) {
     const int32_t word2 = meta[j + 2];
     const int next_tile = word1 & 0xffffff;
     const int32_t next_origin = kNat ? tile_origin[next_tile] : 0;  // requested a phase ahead of the copy that uses it
-    const int cls = (word >> 24) & 0x7f;
+    const int cls = (word >> 24) & 0x7f;  // padding class of the key tile
     // bit 31: keys B/2 .. B-1 of this tile are padding only, the products of the upper key blocks are skipped
     const bool upper_keys = word >= 0;
 
@@ -121,15 +117,7 @@ void attn_bf16_kernel(AttnArgs a) {
     WAIT_VMCNT(S::kLoadsPerThread);  // K(j) landed (V(j) may still be in flight)
     BARRIER();
     floatx16 acc_s[S::kKeyBlocks];
-    w.template qk<0, kLowerBlocks>(k_tile, acc_s);
-    if (upper_keys) {
-      w.template qk<kLowerBlocks, S::kKeyBlocks>(k_tile, acc_s);
-    } else {
-#pragma unroll
-      for (int kb = kLowerBlocks; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_s[kb][r] = kMinusInf;
-    }
+    w.qk_tile(k_tile, acc_s, upper_keys);
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading K(j)
     if (j + 1 < count) src.issue(k_loader, Kp, next_tile, next_origin, lds_k_addr);
@@ -142,8 +130,7 @@ void attn_bf16_kernel(AttnArgs a) {
     if (j + 1 < count) WAIT_VMCNT(S::kLoadsPerThread);  // V(j) landed (K(j+1) may be in flight)
     else WAIT_VMCNT(0);
     BARRIER();
-    w.template pv<0, kLowerBlocks>(v_tile, pf);
-    if (upper_keys) w.template pv<kLowerBlocks, S::kKeyBlocks>(v_tile, pf);
+    w.pv_tile(v_tile, pf, upper_keys);
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V(j)
     if (j + 1 < count) src.issue(v_loader, Vp, next_tile, next_origin, lds_v_addr);
@@ -151,8 +138,7 @@ void attn_bf16_kernel(AttnArgs a) {
     word1 = word2;
   }
 
-  const bool q_real = (q_valid >> w.qi) & 1u;
-  w.store(static_cast<char*>(a.out) + plane + q_row * S::kRowBytes, q_real, !kNat || q_real);
+  w.store(static_cast<char*>(a.out) + plane + q_row * S::kRowBytes, qs.real, !kNat || qs.real);
 }
 
 template <int B, int D>

@@ -21,6 +21,9 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 #define CONST_PTR(T, p) ((const __attribute__((address_space(4))) T*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+#ifndef CA_FMA
+#define CA_FMA 0
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMinusInf = -__builtin_inff();
 constexpr float kLazyLog2 = 8.0f;          // the exponent reference may lag the row max by 2^8
@@ -223,6 +226,30 @@ struct TileSource {
   }
 };
 
+// Which slot of its query tile a lane works for.  Lanes take the tile's slots in the order of
+// class_perm (the slots that hold a token first, then the padding slots), so the queries of a padded
+// tile fill as few 32-query waves as possible and the remaining waves only move tiles.  Every lane
+// still owns exactly one slot, i.e. one row of the output: a padding slot's row is written as zero.
+struct QuerySlot {
+  int slot;          // position in the tile, 0 .. B-1
+  bool real;         // the slot holds a token
+  bool wave_active;  // at least one lane of this wave holds a token (wave-uniform)
+};
+// first: index of the wave's first lane in that order (32 * wave for a tile of its own)
+template <int B>
+__device__ __forceinline__ QuerySlot query_slot(const AttnArgs& a, int64_t q_tile, int first, int qi) {
+  const int cls = CONST_PTR(int32_t, a.tile_class)[q_tile];
+  const auto mask = CONST_PTR(uint32_t, a.class_mask) + cls * 4;
+  int valid = __builtin_popcount(mask[0]) + __builtin_popcount(mask[1]);
+  if (B > 64) valid += __builtin_popcount(mask[2]) + __builtin_popcount(mask[3]);
+  QuerySlot q;
+  q.slot = first + qi;
+  if (cls != 0) q.slot = a.class_perm[cls * 128 + first + qi];
+  q.real = first + qi < valid;
+  q.wave_active = first < valid;
+  return q;
+}
+
 // One wave's 32 queries: operand fragments, accumulators and softmax state, and the tile step.
 //
 // Transposed formulation.  Scores are computed as S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so in
@@ -240,15 +267,17 @@ struct QueryWave {
   bf16x8 qf[S::kQkSteps];      // B operand of S^T: lane (qi, g) holds d = 16*step + 8*g .. +7 of its query
   floatx16 acc_o[S::kDBlocks];
   // Exponent reference of this lane's query (raw score units): the first tile's row maximum,
-  // afterwards a lagging running maximum.  neg_m holds -m_run in all 16 registers and is the C
-  // operand of the first contraction step, so the score accumulator comes out as (score - reference).
+  // afterwards a lagging running maximum.  A probability is exp2(score * c2 + neg_mc2).
+  float m_run, neg_mc2;        // neg_mc2 = -m_run * c2
+#if !CA_FMA
   floatx16 neg_m;
-  float m_run, l_run;          // l_run: this lane's share of the running sum (partner lane holds the rest)
+#endif
+  float l_run;                 // this lane's share of the running sum (partner lane holds the rest)
   float c2, lazy_raw;          // scale * log2(e); kLazyLog2 in raw score units
   int qi, g;
   // per-lane LDS read offsets
   int k_lane_row_off, k_lane_swz;                              // K: row (32*kb + qi), logical chunk 2*step + g
-  int v_lane_row, v_lane_swz, v_lane_chunk, v_lane_half;       // V: transposing read, see pv()
+  int v_lane_row, v_lane_swz, v_lane_chunk, v_lane_half;       // V: transposing read, see read_v()
 
   __device__ __forceinline__ QueryWave(int lane, float scale) {
     qi = lane & 31;
@@ -256,9 +285,12 @@ struct QueryWave {
     c2 = scale * kLog2e;
     lazy_raw = kLazyLog2 / c2;
     m_run = 0.f;
+    neg_mc2 = 0.f;
     l_run = 0.f;
+#if !CA_FMA
 #pragma unroll
     for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
+#endif
 #pragma unroll
     for (int db = 0; db < S::kDBlocks; ++db)
 #pragma unroll
@@ -285,16 +317,41 @@ struct QueryWave {
   }
 
   // ---- S^T = K Q^T for the key blocks [kKb0, kKb1) of the tile in lds_k ------------------------
+  // One accumulator chain per key block, the contraction steps innermost: written in this order the
+  // compiler requests the K fragments of step s + 1 before it issues the products of step s
+  // (measured 2-3 % faster at 128-token tiles than the contraction step outermost).
   template <int kKb0, int kKb1>
   __device__ __forceinline__ void qk(LdsTile lds_k, floatx16 (&acc_s)[S::kKeyBlocks]) const {
+    floatx16 zero;
 #pragma unroll
-    for (int s = 0; s < S::kQkSteps; ++s) {
+    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 #pragma unroll
-      for (int kb = kKb0; kb < kKb1; ++kb) {
+    for (int kb = kKb0; kb < kKb1; ++kb) {
+#pragma unroll
+      for (int s = 0; s < S::kQkSteps; ++s) {
         const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
         const bf16x8 kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(lds_k + off);
+#if CA_FMA
+        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? zero : acc_s[kb], 0, 0, 0);
+#else
         acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
+#endif
       }
+    }
+  }
+
+  // S^T of one tile.  `upper_keys` false: the upper half of the key slots is padding only (a tile on
+  // a padded face of the grid along t); those key blocks are not multiplied, their scores are -inf.
+  __device__ __forceinline__ void qk_tile(LdsTile lds_k, floatx16 (&acc_s)[S::kKeyBlocks], bool upper_keys) const {
+    constexpr int kLower = S::kKeyBlocks / 2;
+    qk<0, kLower>(lds_k, acc_s);
+    if (upper_keys) {
+      qk<kLower, S::kKeyBlocks>(lds_k, acc_s);
+    } else {
+#pragma unroll
+      for (int kb = kLower; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_s[kb][r] = kMinusInf;
     }
   }
 
@@ -322,11 +379,11 @@ struct QueryWave {
   }
 
   // ---- online softmax (one query per lane) -------------------------------------------------------
-  // acc_s holds score - reference in raw units.  The reference is set to the row maximum on the
-  // first tile of the row (`first`, wave-uniform) and afterwards moves only for rows whose maximum
-  // exceeds it by more than 2^kLazyLog2 (probabilities then stay below that factor, far inside fp32
-  // and bf16 range); the accumulator rescale O *= alpha is then a rarely taken wave-uniform branch
-  // and the common path is exp2 alone.  The result is still the exact softmax: numerator and
+  // acc_s holds raw scores.  The exponent reference is set to the row maximum on the first tile of
+  // the row (`first`, wave-uniform) and afterwards moves only for rows whose maximum exceeds it by
+  // more than 2^kLazyLog2 (probabilities then stay below that factor, far inside fp32 and bf16 range);
+  // the accumulator rescale O *= alpha is then a rarely taken wave-uniform branch and the common path
+  // per score is one FMA and one exp2.  The result is still the exact softmax: numerator and
   // denominator share the same reference.  Probabilities are rounded to bf16 (the B operand of the
   // second product); the row sum adds up the rounded values, two per v_dot2, so numerator and
   // denominator see the same numbers.
@@ -337,11 +394,29 @@ struct QueryWave {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
     mx = max_with_partner(mx);
+#if CA_FMA
+    {
+      const float excess = mx - m_run;
+      const uint64_t over = __builtin_amdgcn_ballot_w64(excess > lazy_raw);
+      if (first || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
+        float delta = (first || excess > lazy_raw) ? excess : 0.f;
+        if (mx == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
+        const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
+        m_run += delta;
+        neg_mc2 = -m_run * c2;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < S::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
+      }
+    }
+#else
     {
       const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
       if (first || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
         float delta = (first || mx > lazy_raw) ? mx : 0.f;
-        if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
+        if (delta == kMinusInf) delta = 0.f;
         const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
         m_run += delta;
         l_run *= alpha;
@@ -357,6 +432,7 @@ struct QueryWave {
         for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
       }
     }
+#endif
     bf16x2 ones;
     ones[0] = (__bf16)1.0f;
     ones[1] = (__bf16)1.0f;
@@ -366,7 +442,11 @@ struct QueryWave {
       for (int t = 0; t < 2; ++t) {
         bf16x8 p8;
 #pragma unroll
+#if CA_FMA
+        for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[kb][8 * t + e], c2, neg_mc2));
+#else
         for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(acc_s[kb][8 * t + e] * c2);
+#endif
         pf[kb][t] = p8;
         l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 0, 1), ones, l_run, false);
         l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 2, 3), ones, l_run, false);
@@ -375,27 +455,36 @@ struct QueryWave {
       }
   }
 
-  // ---- O^T += V^T P^T for the key blocks [kKb0, kKb1) of the tile in lds_v ----------------------
+  // ---- O^T += V^T P^T ---------------------------------------------------------------------------
   // V stays row-major [key][d] in LDS and is read with ds_read_b64_tr_b16, which hands each lane
-  // four consecutive keys of one d column, i.e. the A operand of O^T.
+  // four consecutive keys of one d column, i.e. the A operand of O^T for the 16 keys of contraction
+  // step (kb, t) and the d block db.
+  __device__ __forceinline__ bf16x8 read_v(LdsTile lds_v, int kb, int t, int db) const {
+    const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
+    const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
+    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(lds_v + base));
+    const shortx4 hi =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(lds_v + base + 8 * S::kRowBytes));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  }
+
+  // the key blocks [kKb0, kKb1) of the tile in lds_v
   template <int kKb0, int kKb1>
   __device__ __forceinline__ void pv(LdsTile lds_v, const bf16x8 (&pf)[S::kKeyBlocks][2]) {
 #pragma unroll
-    for (int kb = kKb0; kb < kKb1; ++kb) {
+    for (int kb = kKb0; kb < kKb1; ++kb)
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int db = 0; db < S::kDBlocks; ++db) {
-          const int chunk = (db * 4 + v_lane_chunk) ^ v_lane_swz;
-          const int base = (kb * 32 + t * 16 + v_lane_row) * S::kRowBytes + chunk * 16 + v_lane_half;
-          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(lds_v + base));
-          const shortx4 hi =
-              __builtin_amdgcn_ds_read_tr16_b64_v4i16((shortx4 __attribute__((address_space(3)))*)(lds_v + base + 8 * S::kRowBytes));
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], acc_o[db], 0, 0, 0);
-        }
-      }
-    }
+        for (int db = 0; db < S::kDBlocks; ++db)
+          acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v(lds_v, kb, t, db), pf[kb][t], acc_o[db], 0, 0, 0);
+  }
+
+  // O^T += V^T P^T of one tile; the upper key blocks are skipped with their scores (see qk_tile):
+  // their probabilities are exactly zero.
+  __device__ __forceinline__ void pv_tile(LdsTile lds_v, const bf16x8 (&pf)[S::kKeyBlocks][2], bool upper_keys) {
+    pv<0, S::kKeyBlocks / 2>(lds_v, pf);
+    if (upper_keys) pv<S::kKeyBlocks / 2, S::kKeyBlocks>(lds_v, pf);
   }
 
   // ---- epilogue: O = O^T / l; a padding query (q_real false) and an empty row give zeros ---------

@@ -62,15 +62,13 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const int64_t begin = a.pair_walk_ptr ? a.pair_walk_ptr[item] : 0;
   const int count = (int)(a.pair_walk_ptr ? a.pair_walk_ptr[item + 1] - begin : a.n);
   const auto walk = CONST_PTR(int32_t, a.pair_walk + begin);
-  const auto tile_class = CONST_PTR(int32_t, a.tile_class);
   const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
 
-  const uint32_t q_valid = class_mask[tile_class[q_tile] * 4 + block];
-  // a wave without a query tile (odd tile count) or without real queries only moves tiles
-  const bool wave_active = q_valid != 0 && (member == 0 || has_b);
-
   QueryWave<S> w(lane, a.scale);
-  const int64_t q_row = kNat ? src.query_row(a, q_tile, block * 32 + w.qi) : q_tile * S::B + block * 32 + w.qi;
+  const QuerySlot qs = query_slot<S::B>(a, q_tile, block * 32, w.qi);
+  // a wave without a query tile (odd tile count) or without real queries only moves tiles
+  const bool wave_active = qs.wave_active && (member == 0 || has_b);
+  const int64_t q_row = kNat ? src.query_row(a, q_tile, qs.slot) : q_tile * S::B + qs.slot;
   w.load_q(static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes);
   bool seen = false;  // this wave has processed a tile of its own list (wave-uniform)
 
@@ -94,13 +92,13 @@ void attn_bf16_pair_kernel(AttnArgs a) {
     const int32_t next_origin = kNat ? tile_origin[next_tile] : 0;
     const bool more = j + 1 < count;
     const bool mine = wave_active && ((word >> (30 + member)) & 1);
-    const int cls = (word >> 24) & 0x3f;
+    const int cls = (word >> 24) & 0x3f;  // padding class of the key tile
 
     // ---- S^T = K Q^T ----------------------------------------------------------------------
     WAIT_VMCNT(S::kLoadsPerThread);  // K landed (V may still be in flight)
     BARRIER();
     floatx16 acc_s[S::kKeyBlocks];
-    if (mine) w.template qk<0, S::kKeyBlocks>(k_tile, acc_s);
+    if (mine) w.qk_tile(k_tile, acc_s, true);
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading K
     if (more) src.issue(k_loader, Kp, next_tile, next_origin, lds_k_addr);
@@ -116,7 +114,7 @@ void attn_bf16_pair_kernel(AttnArgs a) {
     if (more) WAIT_VMCNT(S::kLoadsPerThread);  // V landed (the next K may be in flight)
     else WAIT_VMCNT(0);
     BARRIER();
-    if (mine) w.template pv<0, S::kKeyBlocks>(v_tile, pf);
+    if (mine) w.pv_tile(v_tile, pf, true);
     WAIT_LGKMCNT0();
     BARRIER();  // every wave has finished reading V
     if (more) src.issue(v_loader, Vp, next_tile, next_origin, lds_v_addr);
@@ -125,8 +123,7 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   }
 
   if (member && !has_b) return;
-  const bool q_real = (q_valid >> w.qi) & 1u;
-  w.store(static_cast<char*>(a.out) + plane + q_row * S::kRowBytes, q_real, !kNat || q_real);
+  w.store(static_cast<char*>(a.out) + plane + q_row * S::kRowBytes, qs.real, !kNat || qs.real);
 }
 
 }  // namespace

@@ -36,6 +36,7 @@ struct AttnArgs {
                                 // readable two words past the last entry
   const int32_t* tile_class;   // device [n]
   const SlotMask* class_mask;  // device
+  const uint8_t* class_perm;   // device [num_classes * 128]; per class: valid slots ascending, then padding slots ascending
   int32_t batch, num_heads;
   int64_t n;                   // tiles
   int32_t B, D;

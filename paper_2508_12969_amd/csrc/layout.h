@@ -31,6 +31,7 @@ struct DeviceTables {
   int32_t* dense_pair_walk = nullptr; // [n + 2] the walk 0..n-1 kept by both tiles (dense path)
   int32_t* tile_class = nullptr; // [n] index into class_mask; 0 = every slot holds a token
   SlotMask* class_mask = nullptr; // [num_classes]
+  uint8_t* class_perm = nullptr;  // [num_classes * 128] per class: its valid slots ascending, then its padding slots ascending
   int32_t* tile_origin = nullptr; // [n] natural-order row of slot 0 of every tile
 };
 
@@ -65,7 +66,7 @@ struct ca_layout {
   std::vector<unsigned char> static_image;
   struct StaticOffsets {
     size_t row_ptr = 0, col_meta = 0, order = 0, pair_rows = 0, pair_walk_ptr = 0, pair_walk = 0, tile_class = 0,
-           class_mask = 0;
+           class_mask = 0, class_perm = 0;
   } static_off;
 };
 
