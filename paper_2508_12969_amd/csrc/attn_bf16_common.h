@@ -21,9 +21,6 @@ typedef __attribute__((ext_vector_type(4))) short shortx4;
 #define CONST_PTR(T, p) ((const __attribute__((address_space(4))) T*)(p))
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-#ifndef CA_FMA
-#define CA_FMA 0
-#endif
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMinusInf = -__builtin_inff();
 constexpr float kLazyLog2 = 8.0f;          // the exponent reference may lag the row max by 2^8
@@ -267,12 +264,10 @@ struct QueryWave {
   bf16x8 qf[S::kQkSteps];      // B operand of S^T: lane (qi, g) holds d = 16*step + 8*g .. +7 of its query
   floatx16 acc_o[S::kDBlocks];
   // Exponent reference of this lane's query (raw score units): the first tile's row maximum,
-  // afterwards a lagging running maximum.  A probability is exp2(score * c2 + neg_mc2).
-  float m_run, neg_mc2;        // neg_mc2 = -m_run * c2
-#if !CA_FMA
+  // afterwards a lagging running maximum.  neg_m holds -m_run in all 16 registers and is the C
+  // operand of the first contraction step, so the score accumulator comes out as (score - reference).
   floatx16 neg_m;
-#endif
-  float l_run;                 // this lane's share of the running sum (partner lane holds the rest)
+  float m_run, l_run;          // l_run: this lane's share of the running sum (partner lane holds the rest)
   float c2, lazy_raw;          // scale * log2(e); kLazyLog2 in raw score units
   int qi, g;
   // per-lane LDS read offsets
@@ -285,12 +280,9 @@ struct QueryWave {
     c2 = scale * kLog2e;
     lazy_raw = kLazyLog2 / c2;
     m_run = 0.f;
-    neg_mc2 = 0.f;
     l_run = 0.f;
-#if !CA_FMA
 #pragma unroll
     for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
-#endif
 #pragma unroll
     for (int db = 0; db < S::kDBlocks; ++db)
 #pragma unroll
@@ -322,20 +314,13 @@ struct QueryWave {
   // (measured 2-3 % faster at 128-token tiles than the contraction step outermost).
   template <int kKb0, int kKb1>
   __device__ __forceinline__ void qk(LdsTile lds_k, floatx16 (&acc_s)[S::kKeyBlocks]) const {
-    floatx16 zero;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 #pragma unroll
     for (int kb = kKb0; kb < kKb1; ++kb) {
 #pragma unroll
       for (int s = 0; s < S::kQkSteps; ++s) {
         const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
         const bf16x8 kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(lds_k + off);
-#if CA_FMA
-        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? zero : acc_s[kb], 0, 0, 0);
-#else
         acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
-#endif
       }
     }
   }
@@ -379,14 +364,14 @@ struct QueryWave {
   }
 
   // ---- online softmax (one query per lane) -------------------------------------------------------
-  // acc_s holds raw scores.  The exponent reference is set to the row maximum on the first tile of
-  // the row (`first`, wave-uniform) and afterwards moves only for rows whose maximum exceeds it by
-  // more than 2^kLazyLog2 (probabilities then stay below that factor, far inside fp32 and bf16 range);
-  // the accumulator rescale O *= alpha is then a rarely taken wave-uniform branch and the common path
-  // per score is one FMA and one exp2.  The result is still the exact softmax: numerator and
-  // denominator share the same reference.  Probabilities are rounded to bf16 (the B operand of the
-  // second product); the row sum adds up the rounded values, two per v_dot2, so numerator and
-  // denominator see the same numbers.
+  // acc_s holds score - reference in raw units.  The reference is set to the row maximum on the
+  // first tile of the row (`first`, wave-uniform) and afterwards moves only for rows whose maximum
+  // exceeds it by more than 2^kLazyLog2 (probabilities then stay below that factor, far inside fp32
+  // and bf16 range); the accumulator rescale O *= alpha is then a rarely taken wave-uniform branch
+  // and the common path per score is one multiply and one exp2.  The result is still the exact
+  // softmax: numerator and denominator share the same reference.  Probabilities are rounded to bf16
+  // (the B operand of the second product); the row sum adds up the rounded values, two per v_dot2, so
+  // numerator and denominator see the same numbers.
   __device__ __forceinline__ void softmax(floatx16 (&acc_s)[S::kKeyBlocks], bool first, bf16x8 (&pf)[S::kKeyBlocks][2]) {
     float mx = acc_s[0][0];
 #pragma unroll
@@ -394,29 +379,11 @@ struct QueryWave {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
     mx = max_with_partner(mx);
-#if CA_FMA
-    {
-      const float excess = mx - m_run;
-      const uint64_t over = __builtin_amdgcn_ballot_w64(excess > lazy_raw);
-      if (first || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
-        float delta = (first || excess > lazy_raw) ? excess : 0.f;
-        if (mx == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
-        const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
-        m_run += delta;
-        neg_mc2 = -m_run * c2;
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < S::kDBlocks; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
-      }
-    }
-#else
     {
       const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
       if (first || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
         float delta = (first || mx > lazy_raw) ? mx : 0.f;
-        if (delta == kMinusInf) delta = 0.f;
+        if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
         const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
         m_run += delta;
         l_run *= alpha;
@@ -432,7 +399,6 @@ struct QueryWave {
         for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
       }
     }
-#endif
     bf16x2 ones;
     ones[0] = (__bf16)1.0f;
     ones[1] = (__bf16)1.0f;
@@ -442,11 +408,7 @@ struct QueryWave {
       for (int t = 0; t < 2; ++t) {
         bf16x8 p8;
 #pragma unroll
-#if CA_FMA
-        for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[kb][8 * t + e], c2, neg_mc2));
-#else
         for (int e = 0; e < 8; ++e) p8[e] = (__bf16)__builtin_amdgcn_exp2f(acc_s[kb][8 * t + e] * c2);
-#endif
         pf[kb][t] = p8;
         l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 0, 1), ones, l_run, false);
         l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(p8, p8, 2, 3), ones, l_run, false);
