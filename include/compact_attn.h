@@ -255,7 +255,10 @@ int compact_attn_tile_mass(const void* q, const void* k, ca_layout* layout, floa
  * Starting from full coverage, each group's kept region on folded offsets (|dh|, |dw|) is a box with a
  * notch at its far corner, i.e. the union of a wide and a tall window (Eq. 2); the cheapest admissible
  * step over all groups (lower / narrow the box, open / deepen / widen the notch, drop the group) is
- * applied until none is left.  Errors: CA_ERR_INVALID_ARG, CA_ERR_ALLOC. */
+ * applied until none is left.  The groups shrink independently, each on its own masses, but share the
+ * one recall budget tau of the head.  A mass whose video-to-video part sums to zero returns full
+ * coverage (recall 1): there is nothing to rank steps by.  Errors: CA_ERR_INVALID_ARG (null, bad
+ * groups or thresholds, a negative or non-finite mass entry), CA_ERR_ALLOC. */
 int compact_attn_search_head(const ca_layout* layout, const float* mass, const int32_t* group_max_dt,
                              int32_t num_groups, double tau, double lambda, int32_t pattern, ca_group* groups,
                              double* recall, double* kept_fraction);

@@ -58,6 +58,13 @@ def mask_recall(mass, mask):
 #     loop: every live group proposes its cheapest admissible move (lowest ratio, ties by the order
 #     A, C, N0, N1, N2, Z); a group without one is finished; the cheapest proposal overall (ties:
 #     lowest group) is applied; the search ends when no group is live.
+#   * "Independently across frame groups" (Sec. 4.2) is read as: every group owns its region and its
+#     moves and shrinks on its own table of masses, but the recall floor tau is one budget of the
+#     whole head (the paper states a single tau per search), so the groups' proposals compete in one
+#     greedy order and a cheap step of one group can use up the recall a dearer step of another would
+#     have needed.
+#   * A mass with a negative or non-finite entry is an error.  A mass that sums to zero has no
+#     recall to preserve or to lose: no move is admissible and full coverage is returned.
 #   * Pattern families (the three columns of Table 3), each a restriction of the one before:
 #       "dual"          everything above: per group a pair of windows;
 #       "frame_groups"  per group ONE window: moves A, C and Z only;
@@ -182,7 +189,14 @@ def search_head(geom: Geometry, mass, group_max_dt, tau, lam, pattern="dual"):
     head format of oracle.layout, recall and kept fraction over video-to-video tile pairs."""
     if pattern not in PATTERNS:
         raise ValueError(f"pattern must be one of {PATTERNS}")
+    video = np.asarray(mass, dtype=np.float64)[:geom.n_vid, :geom.n_vid]
+    if not np.all(np.isfinite(video)) or np.any(video < 0):
+        raise ValueError("attention mass must be finite and non-negative")
     R, C, lost_mass, lost_pairs = fold_group_tables(geom, mass, group_max_dt)
+    if not (R.sum() + lost_mass > 0):          # nothing to rank the moves by: keep everything
+        full = [(int(d), (geom.nH - 1, geom.nW - 1), (-1, -1)) for d in group_max_dt]
+        total = int(C.sum()) + lost_pairs
+        return full, 1.0, (int(C.sum()) / total if total else 1.0)
     if pattern == "cubic":
         return _search_cubic(geom, R, C, lost_mass, lost_pairs, group_max_dt, tau, lam)
     moves = MOVES if pattern == "dual" else ("A", "C", "Z")

@@ -14,11 +14,16 @@
 //   - Moves: lower the box, narrow the box, open the notch at the corner cell, deepen it, widen it,
 //     or drop the group.  A move must remove at least one tile pair, keep recall >= tau and have a
 //     ratio <= lambda.  Every live group proposes its cheapest such move, the cheapest proposal
-//     overall is applied, a group without a proposal is finished.
+//     overall is applied, a group without a proposal is finished.  The groups shrink independently
+//     (each on its own table, with its own region) but share the head's one recall budget tau, so
+//     their proposals compete in a single greedy order.
+//   - A negative or non-finite mass entry is an error; a mass that sums to zero leaves no recall to
+//     rank moves by, so no move is admissible and full coverage is returned.
 //   - Pattern families (the columns of Table 3): dual windows as above; frame groups with one
 //     window each (no notch moves); a cubic window, i.e. one spatial window shared by all kept
 //     groups plus a temporal radius (lower / narrow it in every kept group at once, or drop the
 //     outermost kept group).
+#include <cmath>
 #include <cstdint>
 #include <vector>
 
@@ -105,6 +110,10 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
         const int i = kh > qh ? kh - qh : qh - kh;
         for (int kw = 0; kw < nW; ++kw, ++k) {
           const int j = kw > qw ? kw - qw : qw - kw;
+          if (!(row[k] >= 0.0f) || std::isinf(row[k])) {
+            set_error("attention mass of tile pair (%lld, %lld) is negative or not finite", (long long)q, (long long)k);
+            return CA_ERR_INVALID_ARG;
+          }
           if (g == G) {
             lost_mass += (double)row[k];
             ++lost_pairs;
@@ -123,10 +132,16 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
     kept_mass += R[c];
     kept_pairs += C[c];
   }
-  // the oracle sums R in array order too (numpy's pairwise order may differ in the last bits only)
+  // kept_mass adds the cells in array order (group, |dh|, |dw| ascending)
   const double total_mass = kept_mass + lost_mass;
   const int64_t total_pairs = kept_pairs + lost_pairs;
-  double recall = total_mass > 0 ? kept_mass / total_mass : 1.0;
+  if (!(total_mass > 0)) {  // nothing to rank the moves by: keep everything
+    for (int g = 0; g < G; ++g) groups_out[g] = ca_group{group_max_dt[g], ca_window{nH - 1, nW - 1}, ca_window{-1, -1}};
+    if (recall_out) *recall_out = 1.0;
+    if (kept_out) *kept_out = total_pairs > 0 ? (double)kept_pairs / (double)total_pairs : 1.0;
+    return CA_OK;
+  }
+  double recall = kept_mass / total_mass;
 
   if (pattern == CA_PATTERN_CUBIC) {
     int h = nH - 1, w = nW - 1, k = G;
@@ -149,7 +164,7 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
               d_mass += R[cell];
             }
         if (pairs == 0) continue;
-        const double d_recall = total_mass > 0 ? d_mass / total_mass : 0.0;
+        const double d_recall = d_mass / total_mass;
         const double ratio = d_recall / ((double)pairs / (double)total_pairs);
         if (ratio > lambda || recall - d_recall < tau) continue;
         if (!have || ratio < best_ratio) have = true, best_ratio = ratio, best_d_recall = d_recall, best_pairs = pairs, best_move = move;
@@ -186,7 +201,7 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
       if (!apply(now, move, &nxt)) continue;
       int64_t pairs = 0;
       double d_mass = 0.0;
-      for (int i = 0; i <= now.h2; ++i)        // ascending (i, j): the order the oracle adds in
+      for (int i = 0; i <= now.h2; ++i)        // removed cells are added in ascending (i, j)
         for (int j = 0; j <= now.w1; ++j)
           if (now.has(i, j) && !nxt.has(i, j)) {
             const size_t cell = ((size_t)g * nH + i) * nW + j;
@@ -194,7 +209,7 @@ int search_head_windows(const ca_layout& L, const float* mass, const int32_t* gr
             d_mass += R[cell];
           }
       if (pairs == 0) continue;
-      const double d_recall = total_mass > 0 ? d_mass / total_mass : 0.0;
+      const double d_recall = d_mass / total_mass;
       const double d_cost = (double)pairs / (double)total_pairs;
       const double ratio = d_recall / d_cost;
       if (ratio > lambda || recall - d_recall < tau) continue;

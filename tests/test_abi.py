@@ -351,6 +351,35 @@ def _pair_cases(draw):
     return T, H, W, tile, n_text, heads
 
 
+def test_search_head_hand_worked_thresholds_and_degenerate_masses():
+    """The library on the hand-worked cases of test_oracle_search.py (the expected windows follow from
+    the arithmetic written there, not from the oracle): the paper's thresholds on a two-density mass,
+    two groups competing for one recall budget, and masses that cannot be searched."""
+    from test_oracle_search import competing_groups_mass, two_density_mass
+    lay = ca.compact_attn_build_layout(1, 6, 6, (1, 1, 1), 0, 1, 1, 64, "bf16", [[]])
+    mass = two_density_mass(Geometry(1, 6, 6, 1, 1, 1, 0))
+    for pattern in ("frame_groups", "dual"):
+        groups, recall, kept = ca.compact_attn_search_head(lay, mass, [0], 0.9, 0.011, pattern)
+        assert groups == [(0, (2, 2), ABSENT)] and kept == (256 + 320) / 1296
+        groups, recall, kept = ca.compact_attn_search_head(lay, mass, [0], 0.9, 0.04, pattern)
+        assert groups == [(0, (1, 1), ABSENT)] and kept == 256 / 1296
+        assert abs(recall - np.float32(5.0109375) * 256 / np.float32(mass).astype(np.float64).sum()) < 1e-9
+    g, mass = competing_groups_mass()
+    lay2 = ca.compact_attn_build_layout(2, 1, 2, (1, 1, 1), 0, 1, 1, 64, "bf16", [[]])
+    for pattern in ("frame_groups", "dual"):
+        groups, recall, kept = ca.compact_attn_search_head(lay2, mass, [0, 1], 0.9, 0.3, pattern)
+        assert groups == [(0, (0, 1), ABSENT), (1, (0, 0), ABSENT)] and abs(recall - 0.95) < 1e-12 and kept == 0.75
+    for pattern in ("cubic", "frame_groups", "dual"):
+        groups, recall, kept = ca.compact_attn_search_head(lay2, np.zeros((4, 4)), [0, 1], 0.9, 0.5, pattern)
+        assert groups == [(0, (0, 1), ABSENT), (1, (0, 1), ABSENT)] and recall == 1.0 and kept == 1.0
+    for value in (np.nan, np.inf, -1.0):
+        bad = np.ones((4, 4), np.float32)
+        bad[1, 2] = value
+        with pytest.raises(ca.CompactAttnError) as e:
+            ca.compact_attn_search_head(lay2, bad, [0, 1], 0.9, 0.5)
+        assert e.value.status == binding.CA_ERR_INVALID_ARG and "mass" in str(e.value)
+
+
 @settings(max_examples=60, deadline=None)
 @given(_pair_cases())
 def test_pair_table_bit_exact(case):

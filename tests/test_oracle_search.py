@@ -176,3 +176,79 @@ def test_pattern_families_on_random_mass_report_their_own_mask():
                 assert flags == sorted(flags, reverse=True)               # kept groups are the innermost ones
     with pytest.raises(ValueError):
         S.search_head(g, mass, [0], 0.9, 0.5, "spiral")
+
+
+# ---------------------------------------------------------------- the paper's thresholds, worked by hand
+
+def two_density_mass(g):
+    """One frame of 6 x 6 unit tiles.  A tile pair at folded offset (|dh|, |dw|) lies in the core
+    (max <= 1), in ring 1 (max == 2) or in ring 2 (max >= 3).  Pair counts per offset are
+    (6-|dh|)(6-|dw|) times 2 per non-zero offset: core 36+60+60+100 = 256, ring 1 48+80+64+48+80 = 320,
+    ring 2 the remaining 720 of 36^2 = 1296.  With 0.03 per ring-1 pair, 0.005 per ring-2 pair and
+    (1296 - 320*0.03 - 720*0.005) / 256 = 5.0109375 per core pair the mean mass per pair is exactly 1,
+    so a step's (delta recall / delta cost) is the mean mass per pair of what it removes: 0.005 for
+    ring-2 cells, 0.03 for ring-1 cells, at least (0.03*64 + 0.005*96) / 160 = 0.015 for any row or
+    column segment that contains a ring-1 cell (the least is cell (2,2) with the ring-2 cells behind
+    it), and above 1 for anything that touches the core."""
+    t, h, w = np.unravel_index(np.arange(g.n), (g.nT, g.nH, g.nW))
+    far = np.maximum(np.abs(h[:, None] - h), np.abs(w[:, None] - w))
+    mass = np.where(far <= 1, 5.0109375, np.where(far == 2, 0.03, 0.005))
+    assert abs(mass.sum() - 1296.0) < 1e-9
+    return mass
+
+
+@pytest.mark.parametrize("pattern", ["frame_groups", "dual"])
+def test_thresholds_of_the_paper_on_a_two_density_mass(pattern):
+    """tau = 0.9 with lambda = 0.011 and 0.04 (the operating points of Table 3 and Sec. 6.2): the ring
+    at 0.5 % of uniform density is cut at both, the ring at 3 % only at lambda = 0.04, the core never;
+    recall stays at 256*5.0109375/1296 = 0.9898 or above, so tau does not bind."""
+    g = _unit_tiles(1, 6, 6)
+    mass = two_density_mass(g)
+    groups, recall, kept = S.search_head(g, mass, [0], 0.9, 0.011, pattern)
+    assert groups == [(0, (2, 2), ABSENT)]
+    assert abs(recall - (1296 - 720 * 0.005) / 1296) < 1e-12 and kept == (256 + 320) / 1296
+    groups, recall, kept = S.search_head(g, mass, [0], 0.9, 0.04, pattern)
+    assert groups == [(0, (1, 1), ABSENT)]
+    assert abs(recall - 256 * 5.0109375 / 1296) < 1e-12 and kept == 256 / 1296
+    groups, recall, kept = S.search_head(g, mass, [0], 0.9, 0.004, pattern)     # below both rings: nothing is cut
+    assert groups == [(0, (5, 5), ABSENT)] and recall == 1.0 and kept == 1.0
+
+
+def competing_groups_mass():
+    """Two frames of 1 x 2 unit tiles, groups at frame distance 0 and 1, total mass 100.  Per group and
+    folded offset |dw| there are 4 tile pairs; masses per cell: group 0: 60 at |dw|=0, 6 at |dw|=1;
+    group 1: 29 at |dw|=0, 5 at |dw|=1.  Narrowing group 0 loses recall 0.06 for cost 4/16 (ratio
+    0.24); narrowing group 1 loses 0.05 (ratio 0.20).  With tau = 0.9 only one of them fits."""
+    g = _unit_tiles(2, 1, 2)
+    t, h, w = np.unravel_index(np.arange(g.n), (g.nT, g.nH, g.nW))
+    dt, dw = np.abs(t[:, None] - t), np.abs(w[:, None] - w)
+    mass = np.where(dt == 0, np.where(dw == 0, 15.0, 1.5), np.where(dw == 0, 7.25, 1.25))
+    assert mass.sum() == 100.0
+    return g, mass
+
+
+@pytest.mark.parametrize("pattern", ["frame_groups", "dual"])
+def test_groups_compete_for_one_recall_budget(pattern):
+    """The cheaper step (group 1, ratio 0.20) is taken first and leaves recall 0.95; the step of group 0
+    would then go to 0.89 < tau and is refused.  A search with a recall budget per group, or one that
+    took steps in group order, would narrow group 0 instead or as well."""
+    g, mass = competing_groups_mass()
+    groups, recall, kept = S.search_head(g, mass, [0, 1], 0.9, 0.3, pattern)
+    assert groups == [(0, (0, 1), ABSENT), (1, (0, 0), ABSENT)]
+    assert abs(recall - 0.95) < 1e-12 and kept == 12 / 16
+    groups, recall, _ = S.search_head(g, mass, [0, 1], 0.85, 0.3, pattern)       # room for both
+    assert groups == [(0, (0, 0), ABSENT), (1, (0, 0), ABSENT)] and abs(recall - 0.89) < 1e-12
+    groups, recall, _ = S.search_head(g, mass, [0, 1], 0.9, 0.21, pattern)       # lambda refuses group 0's step anyway
+    assert groups == [(0, (0, 1), ABSENT), (1, (0, 0), ABSENT)]
+
+
+def test_degenerate_masses():
+    g = _unit_tiles(2, 3, 3)
+    for pattern in S.PATTERNS:
+        groups, recall, kept = S.search_head(g, np.zeros((g.n, g.n)), [0, 1], 0.9, 0.5, pattern)
+        assert groups == [(0, (2, 2), ABSENT), (1, (2, 2), ABSENT)] and recall == 1.0 and kept == 1.0
+    bad = np.ones((g.n, g.n))
+    for value in (np.nan, np.inf, -1.0):
+        bad[3, 4] = value
+        with pytest.raises(ValueError):
+            S.search_head(g, bad, [0, 1], 0.9, 0.5)
