@@ -80,87 +80,6 @@ void free_device_tables(ca::DeviceTables& d) {
   d = ca::DeviceTables{};
 }
 
-// Host images of the tables the kernels read, packed from the layout's host tables.
-struct PackedTables {
-  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk, tile_origin;
-  std::vector<uint8_t> class_perm;
-};
-
-// The kernels read one packed word per kept tile: tile id | padding class << 24, and bit 31 set
-// when the upper half of the tile's slots is padding only (such a tile costs half the products).
-// `forward_only` leaves out what only the dense and the natural-order walks read.
-int pack_tables(const ca_layout* L, bool forward_only, PackedTables& t) {
-  if (L->n >= (int64_t)1 << 24 || L->class_mask.size() > 127) {
-    set_error("layout too large for the device tables (%lld tiles, %zu padding classes)", (long long)L->n,
-              L->class_mask.size());
-    return CA_ERR_UNSUPPORTED;
-  }
-  try {
-    std::vector<uint32_t> class_word(L->class_mask.size());
-    const int words = (int)((L->B + 31) / 32);
-    for (size_t c = 0; c < class_word.size(); ++c) {
-      bool upper_empty = words >= 2;
-      for (int w = words / 2; w < words; ++w) upper_empty = upper_empty && L->class_mask[c].w[w] == 0;
-      class_word[c] = ((uint32_t)c << 24) | (upper_empty ? 0x80000000u : 0u);
-    }
-    // Query slots of a tile in the order the bf16 kernels hand them to lanes: the slots that hold a
-    // token first, so that the queries of a padded tile fill as few 32-query waves as possible.
-    t.class_perm.assign(L->class_mask.size() * 128, 0);
-    for (size_t c = 0; c < L->class_mask.size(); ++c) {
-      int at = 0;
-      for (int pass = 0; pass < 2; ++pass)
-        for (int slot = 0; slot < (int)L->B && slot < 128; ++slot) {
-          const bool valid = (L->class_mask[c].w[slot >> 5] >> (slot & 31)) & 1u;
-          if (valid == (pass == 0)) t.class_perm[c * 128 + at++] = (uint8_t)slot;
-        }
-    }
-    // two words of padding: the kernels fetch these tables two entries ahead of the one in use
-    t.col_meta.assign(L->col_idx.size() + 2, 0);
-    for (size_t i = 0; i < L->col_idx.size(); ++i)
-      t.col_meta[i] = (int32_t)((uint32_t)L->col_idx[i] | class_word[L->tile_class[L->col_idx[i]]]);
-    if (!forward_only) {
-      t.dense_meta.assign(L->n + 2, 0);
-      for (int64_t i = 0; i < L->n; ++i) t.dense_meta[i] = (int32_t)((uint32_t)i | class_word[L->tile_class[i]]);
-      // natural-order row of slot 0 of every tile (kernels that gather tiles from natural order)
-      const ca_problem& pr = L->prob;
-      const int64_t n_video = (int64_t)pr.T * pr.H * pr.W;
-      if (L->N_real < ((int64_t)1 << 31)) {
-        t.tile_origin.resize(L->n);
-        for (int64_t i = 0; i < L->n; ++i) {
-          if (i >= L->n_vid) {
-            t.tile_origin[i] = (int32_t)(n_video + (i - L->n_vid) * L->B);
-          } else {
-            const int64_t kw = i % L->nW, kh = (i / L->nW) % L->nH, kt = i / ((int64_t)L->nW * L->nH);
-            t.tile_origin[i] = (int32_t)(((kt * pr.tt) * pr.H + kh * pr.th) * pr.W + kw * pr.tw);
-          }
-        }
-      }
-    }
-    if (!L->pair_rows.empty()) {
-      // walk words of the paired kernel carry the class in bits 24-29, below the two membership bits
-      if (L->class_mask.size() > 63) {
-        set_error("layout has too many padding classes for the paired kernel (%zu)", L->class_mask.size());
-        return CA_ERR_UNSUPPORTED;
-      }
-      t.pair_walk.assign(L->pair_walk.size() + 2, 0);
-      for (size_t i = 0; i < L->pair_walk.size(); ++i) {
-        const uint32_t w = (uint32_t)L->pair_walk[i];
-        t.pair_walk[i] = (int32_t)(w | ((uint32_t)L->tile_class[w & 0xffffffu] << 24));
-      }
-      if (!forward_only) {
-        t.dense_pair_walk.assign(L->n + 2, 0);
-        for (int64_t i = 0; i < L->n; ++i)
-          t.dense_pair_walk[i] =
-              (int32_t)((uint32_t)i | ((uint32_t)L->tile_class[i] << 24) | ca::kPairInFirst | ca::kPairInSecond);
-      }
-    }
-  } catch (const std::bad_alloc&) {
-    set_error("out of host memory while packing the device tables");
-    return CA_ERR_ALLOC;
-  }
-  return CA_OK;
-}
-
 // Makes sure the layout's tables are on the current device.  The first call for a layout allocates
 // device memory and copies synchronously, which a stream under capture must not see: there the call
 // fails and names compact_attn_layout_upload instead.
@@ -186,8 +105,8 @@ int ensure_uploaded(ca_layout* L, hipStream_t stream) {
       return CA_ERR_INVALID_ARG;
     }
   }
-  PackedTables t;
-  int st = pack_tables(L, false, t);
+  ca::PackedTables t;
+  int st = ca::pack_device_tables(*L, false, t);
   if (st != CA_OK) return st;
   ca::DeviceTables d;
   st = upload_vec(L->row_ptr.data(), L->row_ptr.size(), &d.row_ptr);
@@ -314,8 +233,8 @@ int run_attention(const void* q, const void* k, const void* v, ca_layout* L, voi
 // Packs the sparse forward's tables into L->static_image (once per layout).  Caller holds g_scratch_mutex.
 int build_static_image(ca_layout* L) {
   if (!L->static_image.empty()) return CA_OK;
-  PackedTables t;
-  int st = pack_tables(L, true, t);
+  ca::PackedTables t;
+  int st = ca::pack_device_tables(*L, true, t);
   if (st != CA_OK) return st;
   auto aligned = [](size_t x) { return (x + 255) & ~(size_t)255; };
   struct Part {

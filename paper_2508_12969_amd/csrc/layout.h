@@ -87,6 +87,13 @@ double head_similarity(const ca_layout& a, int32_t ha, const ca_layout& b, int32
 // Window search of one head (search.cpp); mass is host float [n*n], groups_out has num_groups entries.
 int search_head_windows(const ca_layout& L, const float* mass, const int32_t* group_max_dt, int32_t num_groups, double tau,
                         double lambda, int32_t pattern, ca_group* groups_out, double* recall_out, double* kept_out);
+// Host images of the tables the kernels read, packed from the layout's host tables (no HIP calls).
+struct PackedTables {
+  std::vector<int32_t> col_meta, dense_meta, pair_walk, dense_pair_walk, tile_origin;
+  std::vector<uint8_t> class_perm;
+};
+// `forward_only` leaves out what only the dense and the natural-order walks read.  Returns a ca_status.
+int pack_device_tables(const ca_layout& layout, bool forward_only, PackedTables& t);
 // Derived tables (per-head views, launch order, padding classes) once row_ptr / col_idx are set.
 void finish_host_tables(ca_layout& L);
 
