@@ -27,8 +27,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # so the figure is a recorded measurement, not one taken live: it is printed with the summary file
 # it comes from, and as null for a workload without a committed counter run.
 RECORDED_TRAFFIC = {
-    "cfg4-S65": {"bytes": 116.4e9, "source": "profiles/attn_bf16_kernel_cfg4-S65_pmc.md"},
-    "cfg3": {"bytes": 62.6e9, "source": "profiles/attn_bf16_pair_kernel_cfg3.md"},
+    "cfg4-S65": {"bytes": 130.4e9, "source": "profiles/attn_bf16_kernel_cfg4-S65_pmc.md"},
+    "cfg3": {"bytes": 57.3e9, "source": "profiles/attn_bf16_pair_kernel_cfg3.md"},
 }
 OTHER_CONFIGS = ("cfg4-S50", "cfg4-S80", "cfg3", "cfg5")
 
@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--pattern-report", action="store_true",
                     help="also search masks under the three pattern families of Table 3 on structured synthetic heads "
                          "and report the sparsity each family reaches")
+    ap.add_argument("--context-calls", type=int, default=3,
+                    help="timed calls of the forward on all-zero inputs and of a plain device copy (0 = skip)")
     ap.add_argument("--other-calls", type=int, default=5,
                     help="timed sparse forward calls on each of the other configurations (cfg4 at 50 %% and 80 %% "
                          "sparsity, cfg3, cfg5), each with the dense kernel at the same shape beside it (0 = skip)")
@@ -58,9 +60,9 @@ def parse():
 
 
 def executed_fraction(ca, lay, wl):
-    """Share of the nominal matrix products the kernel really issues: a 32-key block or a 32-query
-    wave that holds padding only is skipped, which happens for tiles on a padded face of the grid
-    whose upper half of slots is empty."""
+    """Share of the nominal matrix products the kernel really issues.  The queries of a padded tile
+    are packed into as few 32-query waves as possible and the remaining waves skip their products;
+    on the key side the upper half of a tile's key blocks is skipped when it holds padding only."""
     import numpy as np
     tt, th, tw = wl.tile
     B = tt * th * tw
@@ -75,7 +77,7 @@ def executed_fraction(ca, lay, wl):
              & (wf[:, None] * tw + c[None] < wl.W))                # [n_vid, B]
     valid = np.concatenate([valid, np.ones((lay.n_tiles - n_vid, B), bool)])
     blocks = valid.reshape(lay.n_tiles, B // 32, 32).any(axis=2)    # [n, B/32]
-    q_waves = blocks.sum(axis=1) / (B // 32)                        # active query waves of a tile
+    q_waves = np.ceil(valid.sum(axis=1) / 32) / (B // 32)           # active query waves of a tile
     k_share = np.where(blocks[:, B // 64:].any(axis=1), 1.0, 0.5)   # upper key half skipped when empty
     done = 0.0
     for h in range(wl.num_heads):
@@ -188,6 +190,20 @@ def main():
     out = torch.empty_like(q)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def median_ms(fn, calls):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(calls):
+            a, b = ev(), ev()
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts)[len(ts) // 2]
+
     n_ev = args.steps
     e_fwd = [(ev(), ev()) for _ in range(n_ev)]
     e_perm = [(ev(), ev()) for _ in range(n_ev)]
@@ -242,6 +258,21 @@ def main():
             ts.append(a.elapsed_time(b))
         dense_ms = sorted(ts)[len(ts) // 2]
 
+    # What the chip's power management does to this kernel: the same launch on all-zero q, k, v (no
+    # operand bit ever toggles in the matrix pipes) and a plain device-to-device copy of one tensor,
+    # the practical ceiling the permutation is measured against.
+    context = {}
+    if args.context_calls > 0:
+        zq, zk, zv = (torch.zeros_like(qp) for _ in range(3))
+        context["attn_ms_all_zero_inputs"] = median_ms(lambda: ca.compact_attn_forward(zq, zk, zv, lay, out=op), args.context_calls)
+        context["attn_frac_all_zero_inputs"] = flops / context["attn_ms_all_zero_inputs"] / 1e9 / PEAK_BF16_TFLOPS
+        del zq, zk, zv
+        scratch = torch.empty_like(qp)
+        copy_ms = median_ms(lambda: scratch.copy_(qp), args.context_calls)
+        context["device_copy_gbps"] = 2 * qp.numel() * esz / copy_ms / 1e6
+        del scratch
+        ca.compact_attn_forward(qp, kp, vp, lay, out=op)
+
     mass = None
     if args.mass_calls > 0 and wl.dtype == "bf16":
         # offline step of the method (Sec. 4.2): attention mass per tile pair, two QK^T walks per row
@@ -281,19 +312,6 @@ def main():
             del o2
         except ca.CompactAttnError as exc:
             fused = {"unsupported": str(exc)}
-
-    def median_ms(fn, calls):
-        fn()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(calls):
-            a, b = ev(), ev()
-            a.record()
-            fn()
-            b.record()
-            torch.cuda.synchronize()
-            ts.append(a.elapsed_time(b))
-        return sorted(ts)[len(ts) // 2]
 
     # The other configurations: the forward and the dense kernel alone, on tile-ordered tensors.
     others = {}
@@ -359,6 +377,7 @@ def main():
                      "traffic_source": RECORDED_TRAFFIC.get(wl.name, {}).get("source"),
                      "algorithmic_flops_per_launch": flops,
                      "algorithmic_bytes_per_launch": 4 * wl.batch * wl.num_heads * lay.n_tokens_padded * D * esz},
+        "context": context or None,
         "tile_mass": mass,
         "fused_gather_scatter": fused,
         "cpu_baseline": cpu,
