@@ -78,3 +78,37 @@ def test_static_forward_fp32_problem():
     got = ca.compact_attn_forward_static(qp, kp, vp, lay)
     torch.cuda.synchronize()
     assert torch.equal(got, want)
+
+
+def test_static_forward_in_a_captured_graph_and_upload_refused_under_capture():
+    """After one call with a layout outside a capture, compact_attn_forward_static enqueues kernels only and
+    can be captured; replays reproduce the eager result.  compact_attn_forward with a layout whose tables
+    are not on the device yet refuses to allocate under capture and names the call to make first."""
+    print("static forward: graph capture", flush=True)
+    heads = [[(0, (1, 1), ABSENT), (1, (0, 0), ABSENT)], [(2, (0, 2), (1, 0))]]
+    wl = make_workload("static-graph", 5, 13, 20, (2, 8, 8), 128, len(heads), 128, "bf16", heads)
+    lay = build_layout(ca, wl)
+    qp, kp, vp = _inputs(wl, lay)
+    want = ca.compact_attn_forward(qp, kp, vp, lay)
+    out = torch.zeros_like(qp)
+    ca.compact_attn_forward_static(qp, kp, vp, lay, out=out)          # stages the tables
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+    fresh = build_layout(ca, wl)                                        # never uploaded
+    other = torch.zeros_like(qp)
+    graph = torch.cuda.CUDAGraph()
+    refused = None
+    with torch.cuda.graph(graph):
+        ca.compact_attn_forward_static(qp, kp, vp, lay, out=out)
+        try:
+            ca.compact_attn_forward(qp, kp, vp, fresh, out=other)
+        except ca.CompactAttnError as exc:
+            refused = exc
+    assert refused is not None and refused.status == -1 and "compact_attn_layout_upload" in str(refused)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
+        _ = (qp.float() * 1.0001).sum().item()                          # eager work between replays
