@@ -231,7 +231,14 @@ int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* l
  *          mass[b, h, a, c] = sum over real query tokens i of tile a and real key tokens j of tile c of
  *          softmax_j(scale * q_i . k_j), the softmax taken over ALL real keys (full attention; the
  *          windows of the layout are ignored, only its geometry and scale are used).
- * Row a of mass sums to the number of real tokens of tile a.  Costs as many FLOPs as one dense pass.
+ * Row a of mass sums to the number of real tokens of tile a.  One Q K^T product per tile pair: half
+ * the FLOPs of one dense pass.
+ *   Workspace: the kernel keeps two floats per (query token, key tile) of the rows in flight.  The
+ *   first call for a layout allocates min(batch * heads * n, 1024) * N_pad * 8 bytes of device
+ *   memory (synchronously; refused with CA_ERR_INVALID_ARG on a stream under capture: call once
+ *   before capturing), which the layout owns until compact_attn_free_layout.  Calls on the same
+ *   layout that overlap in time (different streams) would share that workspace and race: give
+ *   concurrent calls a layout each.  CA_ERR_ALLOC if the allocation fails.
  * Supported: bf16 with (B, D) in {64,128} x {64,128}; otherwise CA_ERR_UNSUPPORTED. */
 int compact_attn_tile_mass(const void* q, const void* k, ca_layout* layout, float* mass, void* stream);
 

@@ -77,6 +77,7 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.class_mask) (void)hipFree(d.class_mask);
   if (d.class_perm) (void)hipFree(d.class_perm);
   if (d.tile_origin) (void)hipFree(d.tile_origin);
+  if (d.mass_partial) (void)hipFree(d.mass_partial);
   d = ca::DeviceTables{};
 }
 
@@ -129,6 +130,38 @@ int ensure_uploaded(ca_layout* L, hipStream_t stream) {
   L->dev = d;
   L->device = dev;
   L->uploaded = true;
+  return CA_OK;
+}
+
+// The tile-mass kernel keeps two floats per (query, key tile) of the rows in flight; its launches cover
+// kMassRowsPerLaunch rows at a time and share one workspace of that many rows, allocated at the
+// first call for the layout (not under capture, like the tables) and freed with it.
+constexpr int64_t kMassRowsPerLaunch = 1024;
+int ensure_mass_workspace(ca_layout* L, hipStream_t stream) {
+  std::lock_guard<std::mutex> lock(L->upload_mutex);
+  if (L->dev.mass_partial) return CA_OK;
+  if (stream) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const hipError_t e = hipStreamIsCapturing(stream, &cap);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
+    if (cap != hipStreamCaptureStatusNone) {
+      set_error("the tile-mass workspace is not allocated yet and the stream is being captured: call "
+                "compact_attn_tile_mass once before the capture");
+      return CA_ERR_INVALID_ARG;
+    }
+  }
+  const int64_t rows_total = (int64_t)L->prob.batch * L->prob.num_heads * L->n;
+  const int64_t rows = rows_total < kMassRowsPerLaunch ? (rows_total > 0 ? rows_total : 1) : kMassRowsPerLaunch;
+  const size_t bytes = (size_t)rows * (size_t)L->N_pad * 2 * sizeof(float);
+  void* p = nullptr;
+  const hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    set_error("hipMalloc of the tile-mass workspace (%zu bytes): %s", bytes, hipGetErrorString(e));
+    return CA_ERR_ALLOC;
+  }
+  L->dev.mass_partial = static_cast<float*>(p);
+  L->dev.mass_partial_rows = rows;
   return CA_OK;
 }
 
@@ -547,14 +580,19 @@ int compact_attn_tile_mass(const void* q, const void* k, ca_layout* L, float* ma
   if ((reinterpret_cast<uintptr_t>(mass) & 3u) != 0) return fail(CA_ERR_INVALID_ARG, "mass must be 4-byte aligned");
   if (ranges_overlap(mass, mass_bytes, q, in_bytes) || ranges_overlap(mass, mass_bytes, k, in_bytes))
     return fail(CA_ERR_INVALID_ARG, "mass must not overlap q or k");
-  const int st = ensure_uploaded(L, (hipStream_t)stream);
+  int st = ensure_uploaded(L, (hipStream_t)stream);
+  if (st == CA_OK) st = ensure_mass_workspace(L, (hipStream_t)stream);
   if (st != CA_OK) return st;
   ca::MassArgs a{};
   a.q = q;
   a.k = k;
   a.mass = mass;
+  a.partial = L->dev.mass_partial;
+  a.partial_rows = L->dev.mass_partial_rows;
+  a.dense_meta = L->dev.dense_meta;
   a.tile_class = L->dev.tile_class;
   a.class_mask = L->dev.class_mask;
+  a.class_perm = L->dev.class_perm;
   a.batch = p.batch;
   a.num_heads = p.num_heads;
   a.n = L->n;

@@ -233,8 +233,8 @@ struct QuerySlot {
   bool wave_active;  // at least one lane of this wave holds a token (wave-uniform)
 };
 // first: index of the wave's first lane in that order (32 * wave for a tile of its own)
-template <int B>
-__device__ __forceinline__ QuerySlot query_slot(const AttnArgs& a, int64_t q_tile, int first, int qi) {
+template <int B, class Args>
+__device__ __forceinline__ QuerySlot query_slot(const Args& a, int64_t q_tile, int first, int qi) {
   const int cls = CONST_PTR(int32_t, a.tile_class)[q_tile];
   const auto mask = CONST_PTR(uint32_t, a.class_mask) + cls * 4;
   int valid = __builtin_popcount(mask[0]) + __builtin_popcount(mask[1]);

@@ -58,8 +58,13 @@ struct MassArgs {
   const void* q;               // [batch, heads, N_pad, D] tile order, bf16
   const void* k;
   float* mass;                 // [batch, heads, n, n]
+  float* partial;              // device workspace, partial_rows * n * B * 2 floats: per query and key tile (sum, reference) of the rows of one launch
+  int64_t partial_rows;        // rows (workgroups) per launch
+  int64_t row_base;            // first row of the launch (set by the launcher)
+  const int32_t* dense_meta;   // device [n + 2]; per key tile: tile id | padding class << 24 | bit 31: upper key blocks empty
   const int32_t* tile_class;   // device [n]
   const SlotMask* class_mask;  // device
+  const uint8_t* class_perm;   // device [num_classes * 128]
   int32_t batch, num_heads;
   int64_t n;
   int32_t B, D;

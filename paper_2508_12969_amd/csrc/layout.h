@@ -33,6 +33,8 @@ struct DeviceTables {
   SlotMask* class_mask = nullptr; // [num_classes]
   uint8_t* class_perm = nullptr;  // [num_classes * 128] per class: its valid slots ascending, then its padding slots ascending
   int32_t* tile_origin = nullptr; // [n] natural-order row of slot 0 of every tile
+  float* mass_partial = nullptr;  // workspace of the tile-mass kernel, mass_partial_rows * n * B * 2 floats; allocated at its first call
+  int64_t mass_partial_rows = 0;
 };
 
 }  // namespace ca

@@ -5,14 +5,19 @@
 // over real tokens only (padding queries add nothing, padding keys are never attended).
 //
 // Same decomposition as the attention kernel in attn_bf16.hip: one workgroup per row, a wave owns
-// 32 queries, transposed product S^T = K Q^T so that a lane owns one query, K tiles copied into
-// swizzled LDS, two buffers.  There is no V.  The row is walked twice over all n key tiles:
-//   walk 1  running exponent reference and row sum l_i (lazy reference as in the attention kernel);
-//   walk 2  the scores again, p = exp2(scale' * (s - m_i)) / l_i, summed over the lane's registers,
-//           the wave and the workgroup's waves (fixed order, so the result is run-to-run
-//           identical), one float per key tile.
-// The second product is the price of not storing the N x N scores; the whole call costs as many
-// FLOPs as one dense attention pass.
+// 32 queries, transposed product S^T = K Q^T so that a lane owns one query (QueryWave in
+// attn_bf16_common.h), K tiles copied into swizzled LDS, two buffers.  There is no V.
+//
+// One product per tile pair.  The normaliser l_i of a query is known only after its last key tile,
+// so the walk over the n key tiles keeps what it cannot finish: per query i and key tile b the
+// unnormalised sum  e[b][i] = sum_{j in b} exp2(scale' * (s_ij - m)), together with the exponent
+// reference m it was taken against (the lazy reference of the attention kernel, which moves a few
+// times per row), two floats, written to a workspace in device memory (2 * n * B floats per
+// workgroup; 1 KiB per step against a 32 KB tile copy).  After the walk the workgroup reads its
+// block back, brings every sum to the query's final reference and reduces over the queries,
+//     mass[a, b] = sum_i e[b][i] * exp2(scale' * (m[b][i] - m_i)) / l_i,
+// in a fixed order, so the result is run-to-run identical.  (The alternative without a workspace
+// walks every row twice and multiplies twice; it measured twice the time per product.)
 #include "attn_bf16_common.h"
 
 namespace ca {
@@ -23,161 +28,137 @@ __global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_wave
 void tile_mass_kernel(MassArgs a) {
   using S = Shape<B, D>;
   __shared__ __attribute__((aligned(1024))) char lds_k[2 * S::kTileBytes];
-  __shared__ float lds_part[2][S::kWaves];
+  __shared__ __attribute__((aligned(16))) float lds_inv[B];  // 1 / l_i
+  __shared__ __attribute__((aligned(16))) float lds_ref[B];  // m_i
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qi = lane & 31;  // query column owned by this lane inside the wave's 32 queries
-  const int g = lane >> 5;   // lane group: which half of every 8-key pair this lane holds
 
   const int64_t rows = (int64_t)a.num_heads * a.n;
-  const int64_t row = blockIdx.x % rows;
-  const int64_t batch = blockIdx.x / rows;
+  const int64_t item = a.row_base + blockIdx.x;  // (batch, head, query tile), row-major
+  const int64_t row = item % rows;
+  const int64_t batch = item / rows;
   const int64_t head = row / a.n, q_tile = row - head * a.n;
   const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
   const char* Kp = static_cast<const char*>(a.k) + plane;
-  float* out = a.mass + ((batch * a.num_heads + head) * a.n + q_tile) * a.n;
-  const auto tile_class = CONST_PTR(int32_t, a.tile_class);
+  float* out = a.mass + item * a.n;
+  // this workgroup's block of the workspace: [n][B] pairs (sum, reference)
+  float2* part = reinterpret_cast<float2*>(a.partial) + (int64_t)blockIdx.x * a.n * B;
+  // one packed word per key tile 0..n-1: tile id | padding class << 24 | bit 31: upper key blocks empty
+  const auto meta = CONST_PTR(int32_t, a.dense_meta);
   const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
   const int n = (int)a.n;
 
-  const float c2 = a.scale * kLog2e;
-  const float lazy_raw = kLazyLog2 / c2;
-  const uint32_t q_valid = class_mask[tile_class[q_tile] * 4 + wave];
-  const bool q_real = (q_valid >> qi) & 1u;
+  // A wave without a real query (see query_slot) takes part in the tile copies and barriers only.
+  QueryWave<S> w(lane, a.scale);
+  const QuerySlot qs = query_slot<B>(a, q_tile, wave * 32, w.qi);
+  const bool wave_active = qs.wave_active;
+  w.load_q(static_cast<const char*>(a.q) + plane + (q_tile * B + qs.slot) * S::kRowBytes);
+  const int mine = wave * 32 + w.qi;  // this lane's query in the workspace block and in lds_inv
+  const bool writer = w.g == 0;       // both lanes of a pair hold the query's sum; the lower one stores it
 
-  // Q fragment: B operand of S^T, lane (qi, g) holds d = 16*step + 8*g .. +7 of its query.
-  bf16x8 qf[S::kQkSteps];
-  {
-    const int64_t q_row = q_tile * B + wave * 32 + qi;
-    const char* Qp = static_cast<const char*>(a.q) + plane + q_row * S::kRowBytes + g * 16;
-#pragma unroll
-    for (int s = 0; s < S::kQkSteps; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qp + s * 32);
-    // wait for these loads here: inside the loops the vector-memory counter belongs to the tile copies
-#pragma unroll
-    for (int s = 0; s < S::kQkSteps; ++s) asm volatile("" : "+v"(qf[s]));
-  }
-
-  // exponent reference of this lane's query (raw units); neg_m = -m_run in all 16 registers is the
-  // C operand of the first contraction step, so scores leave the MFMA as (score - reference)
-  float m_run = 0.f, l_run = 0.f;
-  floatx16 neg_m;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
-
-  const int k_lane_row_off = qi * S::kRowBytes;
-  const int k_lane_swz = k_swizzle<D>(qi);
   const TileLoader<S, false> k_loader(wave, lane);
   const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_k;
+  const LdsTile k_tile = (LdsTile)lds_k;
 
-  // scores of key tile j (already in LDS buffer j%2) against this wave's queries, padding keys -inf
-  auto scores = [&](int j, floatx16 (&acc_s)[S::kKeyBlocks]) {
-    const char* kbuf = lds_k + (j & 1) * S::kTileBytes;
-#pragma unroll
-    for (int s = 0; s < S::kQkSteps; ++s) {
-#pragma unroll
-      for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
-        const int off = kb * 32 * S::kRowBytes + k_lane_row_off + (((2 * s + g) ^ k_lane_swz) << 4);
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kbuf + off);
-        acc_s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? neg_m : acc_s[kb], 0, 0, 0);
-      }
-    }
-    const int cls = __builtin_amdgcn_readfirstlane(tile_class[j]);
-    if (cls != 0) {  // wave-uniform: only tiles on a padded face of the grid have invalid slots
-#pragma unroll
-      for (int kb = 0; kb < S::kKeyBlocks; ++kb) {
-        const uint32_t bits = __builtin_amdgcn_readfirstlane(class_mask[cls * 4 + kb]);
-        if (bits != 0xffffffffu) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int bit = 8 * (r / 4) + (r % 4);  // lanes 0-31 hold key 8*(r/4) + r%4 of the block, lanes 32-63 that + 4
-            const uint32_t lo = 0u - ((bits >> bit) & 1u), hi = 0u - ((bits >> (bit + 4)) & 1u);
-            const uint64_t keep = (uint64_t)lo | ((uint64_t)hi << 32);
-            asm("v_cndmask_b32 %0, %1, %0, %2" : "+v"(acc_s[kb][r]) : "v"(kMinusInf), "s"(keep));
-          }
-        }
-      }
-    }
-  };
-  // top of a step: K(j) landed and visible, buffer (j+1)%2 free; start the next copy
-  auto step_begin = [&](int j) {
+  // the packed words are fetched two steps ahead of their use (the table is readable two words past its end)
+  int32_t word = meta[0], word1 = meta[1];
+  k_loader.issue(Kp, lds_k_addr, wave);
+  float2 prev = {0.f, 0.f};  // the previous tile's sum and its reference, stored at the head of the next step
+  float l_row = 0.f;   // the query's running sum over all key tiles (both lanes of a pair hold it)
+
+  for (int j = 0; j < n; ++j) {
+    const int32_t word2 = meta[j + 2];
+    // K(j) landed and visible, buffer (j+1)%2 free, the previous step's store has been written
     WAIT_VMCNT(0);
-    WAIT_LGKMCNT0();  // this wave's partial sum of the previous tile is in LDS
     BARRIER();
     if (j + 1 < n) k_loader.issue(Kp + (int64_t)(j + 1) * S::kTileBytes, lds_k_addr + ((j + 1) & 1) * S::kTileBytes, wave);
-  };
+    if (j > 0 && writer) part[(int64_t)(j - 1) * B + mine] = prev;  // a whole step to complete
 
-  // ---- walk 1: exponent reference and row sum ------------------------------------------------
-  k_loader.issue(Kp, lds_k_addr, wave);
-  for (int j = 0; j < n; ++j) {
-    step_begin(j);
-    floatx16 acc_s[S::kKeyBlocks];
-    scores(j, acc_s);
-    float mx = acc_s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
-    mx = max_with_partner(mx);
-    const uint64_t over = __builtin_amdgcn_ballot_w64(mx > lazy_raw);
-    if (j == 0 || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
-      float delta = (j == 0 || mx > lazy_raw) ? mx : 0.f;
-      if (delta == kMinusInf) delta = 0.f;
-      const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta * c2);
-      m_run += delta;
-      l_run *= alpha;
+    float e = 0.f;
+    if (wave_active) {
+      floatx16 acc_s[S::kKeyBlocks];
+      w.qk_tile(k_tile + (j & 1) * S::kTileBytes, acc_s, word >= 0);
+      w.mask_padding_keys(acc_s, (word >> 24) & 0x7f, class_mask);
+
+      // lazy exponent reference as in QueryWave::softmax: set on the first tile, moved only for rows
+      // whose maximum exceeds it by more than 2^kLazyLog2
+      float mx = acc_s[0][0];
 #pragma unroll
       for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
+      mx = max_with_partner(mx);
+      const uint64_t over = __builtin_amdgcn_ballot_w64(mx > w.lazy_raw);
+      if (j == 0 || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
+        float delta = (j == 0 || mx > w.lazy_raw) ? mx : 0.f;
+        if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
+        const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta * w.c2);
+        w.m_run += delta;
+        l_row *= alpha;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) w.neg_m[r] = -w.m_run;
+      }
+      float e4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e4[r & 3] += __builtin_amdgcn_exp2f(acc_s[kb][r] * w.c2);
+      e = sum_with_partner((e4[0] + e4[1]) + (e4[2] + e4[3]));
+      l_row += e;
     }
-#pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) l_run += __builtin_amdgcn_exp2f(acc_s[kb][r] * c2);
+    prev.x = e;
+    prev.y = w.m_run;
+    word = word1;
+    word1 = word2;
   }
-  const float l_tot = sum_with_partner(l_run);
-  const float inv = (q_real && l_tot > 0.f) ? 1.0f / l_tot : 0.f;
 
-  // ---- walk 2: probabilities summed per key tile -----------------------------------------------
-  BARRIER();  // every wave has left walk 1 before buffer 0 is refilled
-  k_loader.issue(Kp, lds_k_addr, wave);
-  for (int j = 0; j < n; ++j) {
-    step_begin(j);
-    if (j > 0 && threadIdx.x == 0) {  // the partial sums of tile j-1 were published before the barrier
-      float m = 0.f;
-#pragma unroll
-      for (int w = 0; w < S::kWaves; ++w) m += lds_part[(j - 1) & 1][w];
-      out[j - 1] = m;
-    }
-    floatx16 acc_s[S::kKeyBlocks];
-    scores(j, acc_s);
-    float part = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) part += __builtin_amdgcn_exp2f(acc_s[kb][r] * c2);
-    part *= inv;
-#pragma unroll
-    for (int sh = 32; sh >= 1; sh >>= 1) part += __shfl_xor(part, sh, 64);
-    if (lane == 0) lds_part[j & 1][wave] = part;
+  // ---- mass[a, b] = sum_i e[b][i] * exp2(scale' * (m[b][i] - m_i)) / l_i --------------------------
+  if (writer) {
+    part[(int64_t)(n - 1) * B + mine] = prev;
+    lds_inv[mine] = (qs.real && l_row > 0.f) ? 1.0f / l_row : 0.f;  // a padding query adds nothing
+    lds_ref[mine] = w.m_run;
   }
+  __threadfence();  // the stored pairs are read back by other waves of this workgroup
   __syncthreads();
-  if (threadIdx.x == 0) {
-    float m = 0.f;
+  constexpr int kLanesPerTile = B / 4;  // a key tile's B pairs, four per lane
+  constexpr int kTilesPerPass = S::kThreads / kLanesPerTile;
+  const int sub = threadIdx.x / kLanesPerTile, l4 = threadIdx.x % kLanesPerTile;
+  const float4 inv = *reinterpret_cast<const float4*>(&lds_inv[4 * l4]);
+  const float4 ref = *reinterpret_cast<const float4*>(&lds_ref[4 * l4]);
+  const float c2 = w.c2;
+#pragma unroll 4
+  for (int b = sub; b < n; b += kTilesPerPass) {
+    const float4* p = reinterpret_cast<const float4*>(part + (int64_t)b * B + 4 * l4);
+    const float4 p01 = p[0], p23 = p[1];  // (e0, m0, e1, m1), (e2, m2, e3, m3)
+    const float t0 = p01.x * __builtin_amdgcn_exp2f((p01.y - ref.x) * c2) * inv.x;
+    const float t1 = p01.z * __builtin_amdgcn_exp2f((p01.w - ref.y) * c2) * inv.y;
+    const float t2 = p23.x * __builtin_amdgcn_exp2f((p23.y - ref.z) * c2) * inv.z;
+    const float t3 = p23.z * __builtin_amdgcn_exp2f((p23.w - ref.w) * c2) * inv.w;
+    float s = (t0 + t1) + (t2 + t3);
 #pragma unroll
-    for (int w = 0; w < S::kWaves; ++w) m += lds_part[(n - 1) & 1][w];
-    out[n - 1] = m;
+    for (int sh = kLanesPerTile / 2; sh >= 1; sh >>= 1) s += __shfl_xor(s, sh, 64);
+    if (l4 == 0) out[b] = s;
   }
 }
 
 template <int B, int D>
-hipError_t launch(const MassArgs& a, hipStream_t stream) {
+hipError_t launch(MassArgs a, hipStream_t stream) {
+  // The workspace holds a.partial_rows workgroups; launches on one stream run one after another, so
+  // each can use it from the start.
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
-  hipLaunchKernelGGL((tile_mass_kernel<B, D>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
-  return hipGetLastError();
+  for (int64_t base = 0; base < items; base += a.partial_rows) {
+    const int64_t count = items - base < a.partial_rows ? items - base : a.partial_rows;
+    a.row_base = base;
+    hipLaunchKernelGGL((tile_mass_kernel<B, D>), dim3((unsigned)count), dim3(B * 2), 0, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace
@@ -185,7 +166,7 @@ hipError_t launch(const MassArgs& a, hipStream_t stream) {
 hipError_t launch_tile_mass(const MassArgs& a, hipStream_t stream) {
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
   if (items == 0) return hipSuccess;
-  if (items > 0x7fffffff) return hipErrorInvalidValue;
+  if (!a.partial || a.partial_rows < 1 || a.partial_rows > 0x7fffffff) return hipErrorInvalidValue;
   if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
   if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
   if (a.B == 64 && a.D == 128) return launch<64, 128>(a, stream);

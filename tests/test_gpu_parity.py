@@ -414,6 +414,63 @@ def test_tile_mass_matches_the_definition(shape):
             assert err.max() <= MASS_ABS
 
 
+@pytest.mark.parametrize("shape", [(128, (2, 8, 8)), (64, (1, 8, 8))])
+def test_tile_mass_with_a_moving_exponent_reference(shape):
+    """Scores that keep rising along the key-tile walk move the kernel's exponent reference again
+    and again after sums have been stored against earlier references; scores hundreds of units apart
+    push the early sums below fp32 range relative to the final reference.  The definition subtracts
+    the exact row maximum and knows neither."""
+    from oracle import search as OS
+    D, tile = shape
+    _say("tile mass, rising scores", shape)
+    T, H, W = 6, 16, 16
+    B = tile[0] * tile[1] * tile[2]
+    wl = make_workload("massrise", T, H, W, tile, B, 2, D, "bf16", [[]] * 2)
+    g = geometry_of(wl)
+    lay = build_layout(ca, wl)
+    q, k, _ = make_qkv(wl, DEV)
+    tok_tile, _ = g.token_tile_and_slot()
+    pop = np.bincount(tok_tile, minlength=g.n)
+    ramp = torch.tensor(np.asarray(tok_tile), device=DEV, dtype=torch.float32) / g.n
+    for gain, what in ((1.0, "rising"), (40.0, "huge")):
+        kk = (k.float() * (1.0 + 3.0 * gain * ramp[None, None, :, None])).to(k.dtype)
+        qq = (q.float() * (2.0 if gain == 1.0 else 6.0)).to(q.dtype)
+        mass = ca.compact_attn_tile_mass(ca.compact_attn_permute(qq, lay), ca.compact_attn_permute(kk, lay), lay)
+        torch.cuda.synchronize()
+        got = mass[0].double().cpu().numpy()
+        assert np.isfinite(got).all()
+        assert np.allclose(got.sum(axis=2), pop[None, :].repeat(2, 0), atol=1e-2)
+        for h in range(2):
+            want = OS.tile_mass(g, to_f64(qq[0, h]), to_f64(kk[0, h]))
+            err = np.abs(got[h] - want)
+            _say(what, "head", h, "max err", err.max(), "max mass", want.max())
+            assert err.max() <= MASS_ABS
+
+
+def test_tile_mass_over_several_launches():
+    """More (batch, head, query tile) rows than one launch of the kernel covers (1024), with a ragged
+    last launch: every launch reuses the same workspace; rows on both sides of each boundary and in
+    the last launch are compared with the definition, all rows with their closed-form sums."""
+    import dataclasses
+    from oracle import search as OS
+    _say("tile mass, several launches")
+    T, H, W, tile, D, Hd, batch = 6, 32, 32, (1, 8, 8), 64, 6, 2
+    wl = dataclasses.replace(make_workload("masslaunch", T, H, W, tile, 0, Hd, D, "bf16", [[]] * Hd), batch=batch)
+    g = geometry_of(wl)
+    assert batch * Hd * g.n == 1152
+    lay = build_layout(ca, wl)
+    q, k, _ = make_qkv(wl, DEV, q_gain=2.0)
+    mass = ca.compact_attn_tile_mass(ca.compact_attn_permute(q, lay), ca.compact_attn_permute(k, lay), lay)
+    torch.cuda.synchronize()
+    got = mass.double().cpu().numpy()
+    assert np.allclose(got.sum(axis=3), 64.0, atol=1e-2)            # every tile holds 64 tokens
+    for b, h in ((0, 0), (1, 4), (1, 5)):                             # row 1024 is batch 1, head 4, tile 64
+        want = OS.tile_mass(g, to_f64(q[b, h]), to_f64(k[b, h]))
+        err = np.abs(got[b, h] - want)
+        _say("batch", b, "head", h, "max err", err.max())
+        assert err.max() <= MASS_ABS
+
+
 def test_tile_mass_rejects_fp32():
     wl = make_workload("massf", 2, 8, 8, (1, 4, 4), 0, 1, 64, "f32", [[]])
     lay = build_layout(ca, wl)
