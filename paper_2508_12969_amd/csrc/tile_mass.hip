@@ -11,8 +11,7 @@
 // One product per tile pair.  The normaliser l_i of a query is known only after its last key tile,
 // so the walk over the n key tiles keeps what it cannot finish: per query i and key tile b the
 // unnormalised sum  e[b][i] = sum_{j in b} exp2(scale' * (s_ij - m)), together with the exponent
-// reference m it was taken against (the lazy reference of the attention kernel, which moves a few
-// times per row), two floats, written to a workspace in device memory (2 * n * B floats per
+// reference m it was taken against (it moves when a sum outgrows it, rarely), two floats, written to a workspace in device memory (2 * n * B floats per
 // workgroup; 1 KiB per step against a 32 KB tile copy).  After the walk the workgroup reads its
 // block back, brings every sum to the query's final reference and reduces over the queries,
 //     mass[a, b] = sum_i e[b][i] * exp2(scale' * (m[b][i] - m_i)) / l_i,
@@ -22,6 +21,8 @@
 
 namespace ca {
 namespace {
+
+constexpr float kSumLimit = 0x1p40f;  // a tile's row sum beyond this moves the query's exponent reference
 
 template <int B, int D>
 __global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
@@ -81,34 +82,44 @@ void tile_mass_kernel(MassArgs a) {
       w.qk_tile(k_tile + (j & 1) * S::kTileBytes, acc_s, word >= 0);
       w.mask_padding_keys(acc_s, (word >> 24) & 0x7f, class_mask);
 
-      // lazy exponent reference as in QueryWave::softmax: set on the first tile, moved only for rows
-      // whose maximum exceeds it by more than 2^kLazyLog2
-      float mx = acc_s[0][0];
+      // The exponent reference is the first tile's row maximum.  Afterwards no maximum is taken: the
+      // sums are formed against the reference as it stands and only a tile whose row sum leaves
+      // [0, kSumLimit] for some query (it overflows, or is about to) is redone for those queries
+      // with its row maximum as their new reference.  Numerator and denominator of a query always
+      // share one reference after the final pass, so the masses are those of the exact softmax.
+      auto row_sum = [&]() {
+        float e4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
-      mx = max_with_partner(mx);
-      const uint64_t over = __builtin_amdgcn_ballot_w64(mx > w.lazy_raw);
-      if (j == 0 || __builtin_amdgcn_readfirstlane((uint32_t)over | (uint32_t)(over >> 32)) != 0) {
-        float delta = (j == 0 || mx > w.lazy_raw) ? mx : 0.f;
+          for (int r = 0; r < 16; ++r) e4[r & 3] += __builtin_amdgcn_exp2f(acc_s[kb][r] * w.c2);
+        return sum_with_partner((e4[0] + e4[1]) + (e4[2] + e4[3]));
+      };
+      bool move = true;  // this lane's query takes a new reference (every query on the first tile)
+      if (j > 0) {
+        e = row_sum();
+        move = !(e <= kSumLimit);  // also true for inf and NaN
+      }
+      const uint64_t movers = __builtin_amdgcn_ballot_w64(move);
+      if (__builtin_amdgcn_readfirstlane((uint32_t)movers | (uint32_t)(movers >> 32)) != 0) {
+        float mx = acc_s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < S::kKeyBlocks; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[kb][r]);
+        mx = max_with_partner(mx);
+        float delta = move ? mx : 0.f;
         if (delta == kMinusInf) delta = 0.f;  // a row that has seen no real key yet keeps its reference
-        const float alpha = j == 0 ? 1.0f : __builtin_amdgcn_exp2f(-delta * w.c2);
         w.m_run += delta;
-        l_row *= alpha;
+        l_row *= __builtin_amdgcn_exp2f(-delta * w.c2);
 #pragma unroll
         for (int kb = 0; kb < S::kKeyBlocks; ++kb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc_s[kb][r] -= delta;
 #pragma unroll
         for (int r = 0; r < 16; ++r) w.neg_m[r] = -w.m_run;
+        e = row_sum();
       }
-      float e4[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kb = 0; kb < S::kKeyBlocks; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e4[r & 3] += __builtin_amdgcn_exp2f(acc_s[kb][r] * w.c2);
-      e = sum_with_partner((e4[0] + e4[1]) + (e4[2] + e4[3]));
       l_row += e;
     }
     prev.x = e;
