@@ -471,6 +471,37 @@ def test_tile_mass_over_several_launches():
         assert err.max() <= MASS_ABS
 
 
+def test_tile_mass_in_a_captured_graph():
+    """The first call for a layout allocates the kernel's workspace and is refused on a stream under
+    capture; after one eager call the same call enqueues kernels only, and replays of the captured
+    graph reproduce the eager masses (the workspace is reused by every replay)."""
+    _say("tile mass, graph capture")
+    wl = make_workload("massgraph", 4, 16, 16, (2, 8, 8), 128, 2, 128, "bf16", [[]] * 2)
+    lay, fresh = build_layout(ca, wl), build_layout(ca, wl)
+    q, k, _ = make_qkv(wl, DEV, q_gain=2.0)
+    qp, kp = ca.compact_attn_permute(q, lay), ca.compact_attn_permute(k, lay)
+    want = ca.compact_attn_tile_mass(qp, kp, lay)
+    ca.compact_attn_layout_upload(fresh)                                # tables there, workspace not
+    torch.cuda.synchronize()
+    out, other = torch.zeros_like(want), torch.zeros_like(want)
+    graph = torch.cuda.CUDAGraph()
+    refused = None
+    with torch.cuda.graph(graph):
+        ca.compact_attn_tile_mass(qp, kp, lay, out=out)
+        try:
+            ca.compact_attn_tile_mass(qp, kp, fresh, out=other)
+        except ca.CompactAttnError as exc:
+            refused = exc
+    assert refused is not None and refused.status == -1 and "workspace" in str(refused)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
+        _ = (qp.float() * 1.0001).sum().item()                          # eager work between replays
+
+
 def test_tile_mass_rejects_fp32():
     wl = make_workload("massf", 2, 8, 8, (1, 4, 4), 0, 1, 64, "f32", [[]])
     lay = build_layout(ca, wl)
