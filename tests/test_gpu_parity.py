@@ -471,6 +471,41 @@ def test_tile_mass_over_several_launches():
         assert err.max() <= MASS_ABS
 
 
+@pytest.mark.parametrize("name", ["cfg3", "cfg4-S65"])
+def test_tile_mass_every_pair_at_full_size_two_level_probe(name):
+    """Every tile pair of every head at the benchmark sizes (24 and 50 launches per call).  Queries
+    are one constant vector and a key's only non-zero component says whether its tile id is odd, so
+    the softmax of every query has two levels, p_j = w^[tile(j) odd] / Z with w = exp(scale * 32)
+    and Z = (real keys in even tiles) + w * (real keys in odd tiles), and the mass of a pair is
+    pop[a] * pop[b] * w^[b odd] / Z: a closed form from the tile populations alone.  With q = 0 it
+    is the uniform pop[a] * pop[b] / N."""
+    wl = get_workload(name)
+    _say("tile mass, all pairs", name)
+    g = geometry_of(wl)
+    D, Hd = wl.head_dim, wl.num_heads
+    lay = build_layout(ca, wl)
+    tok_tile = g.token_slots() // g.B
+    pop = np.bincount(tok_tile, minlength=g.n).astype(np.float64)
+    odd = (np.arange(g.n) % 2).astype(np.float64)
+    q = torch.zeros(1, Hd, g.N_real, D, dtype=torch.bfloat16, device=DEV)
+    k = torch.zeros(1, Hd, g.N_real, D, dtype=torch.bfloat16, device=DEV)
+    k[..., 0] = torch.from_numpy(odd[tok_tile]).to(DEV).to(torch.bfloat16)
+    kp = ca.compact_attn_permute(k, lay)
+    del k
+    scale = 1.0 / np.sqrt(D)
+    for q0 in (0.0, 32.0):
+        q[..., 0] = q0
+        mass = ca.compact_attn_tile_mass(ca.compact_attn_permute(q, lay), kp, lay)
+        torch.cuda.synchronize()
+        w = np.exp(scale * q0 * odd)                                   # per key tile
+        want = np.outer(pop, pop * w) / float((pop * w).sum())        # [n, n], the same for every head
+        want_dev = torch.from_numpy(want).to(DEV).float()
+        worst = max((mass[0, h] - want_dev).abs().max().item() for h in range(Hd))
+        _say(name, "q0", q0, "worst abs err over all pairs", worst, "largest mass", want.max())
+        assert worst <= MASS_ABS
+        del mass
+
+
 def test_tile_mass_in_a_captured_graph():
     """The first call for a layout allocates the kernel's workspace and is refused on a stream under
     capture; after one eager call the same call enqueues kernels only, and replays of the captured
