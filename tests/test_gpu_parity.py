@@ -669,6 +669,73 @@ def test_forward_natural_rejects_what_it_does_not_cover():
         ca.compact_attn_forward_natural(q, k, v, lay)
 
 
+# ---------------------------------------------------------------- random problems
+
+_TILE_SHAPES = {64: [(1, 8, 8), (2, 4, 8), (1, 4, 16), (4, 4, 4), (1, 16, 4), (2, 8, 4)],
+                128: [(2, 8, 8), (1, 8, 16), (1, 16, 8), (4, 4, 8), (2, 4, 16), (8, 4, 4)]}
+
+
+def _random_problem(seed):
+    """A seeded random problem: tile shape, ragged grid, text tiles, 1-3 heads with up to three frame
+    groups of clipped or clamped windows (absent windows and empty heads included), batch 1-2."""
+    rng = np.random.default_rng(seed)
+    B, D = int(rng.choice([64, 128])), int(rng.choice([64, 128]))
+    tile = _TILE_SHAPES[B][int(rng.integers(len(_TILE_SHAPES[B])))]
+    T, H, W = int(rng.integers(1, 4 * tile[0] + 2)), int(rng.integers(3, 4 * tile[1] + 3)), int(rng.integers(3, 3 * tile[2] + 5))
+    while T * H * W > 9000:
+        H, W = max(3, H - 3), max(3, W - 3)
+    n_text = int(rng.choice([0, 0, B, 2 * B]))
+    Hd, batch = int(rng.integers(1, 4)), int(rng.choice([1, 1, 2]))
+    heads = []
+    for _ in range(Hd):
+        if rng.integers(4) == 0:
+            heads.append([])
+            continue
+        groups = []
+        for dt in sorted(set(int(x) for x in rng.integers(0, 6, int(rng.integers(1, 4))))):
+            a = (int(rng.integers(-1, 4)), int(rng.integers(-1, 4)))
+            b = (int(rng.integers(-1, 4)), int(rng.integers(-1, 4)))
+            groups.append((dt, a if min(a) >= 0 else ABSENT, b if min(b) >= 0 else ABSENT))
+        heads.append(groups)
+    clamp = [bool(rng.integers(2)) for _ in range(Hd)]
+    return B, D, tile, (T, H, W), n_text, batch, heads, clamp, float(rng.choice([1.0, 2.0, 3.0]))
+
+
+@pytest.mark.parametrize("first_seed", [0, 8, 16])
+def test_random_problems_through_every_entry_point(first_seed):
+    """Eight seeded random problems per case through permute, sparse forward, dense, the natural-order
+    forward, the allocation-free forward and the tile mass, each against the oracle (the last two
+    forwards bit for bit against the first)."""
+    import dataclasses
+    from oracle import search as OS
+    for seed in range(first_seed, first_seed + 8):
+        B, D, tile, (T, H, W), n_text, batch, heads, clamp, gain = _random_problem(seed)
+        _say("random problem", seed, B, D, tile, (T, H, W), n_text, batch, heads, clamp)
+        Hd = len(heads)
+        wl = dataclasses.replace(make_workload("random", T, H, W, tile, n_text, Hd, D, "bf16", heads), batch=batch)
+        g = geometry_of(wl)
+        lay = ca.compact_attn_build_layout(T, H, W, tile, n_text, batch, Hd, D, "bf16", heads, clamp_centre=clamp)
+        oracle_heads = [OL.ClampedHead(h) if c else h for h, c in zip(heads, clamp)]
+        q, k, v = make_qkv(wl, DEV, q_gain=gain)
+        out, out_tiled = gpu_attention(ca, wl, lay, q, k, v)
+        dense, _ = gpu_attention(ca, wl, lay, q, k, v, dense=True)
+        qp, kp, vp = (ca.compact_attn_permute(t, lay) for t in (q, k, v))
+        mass = ca.compact_attn_tile_mass(qp, kp, lay)
+        if tile[2] % (4 if D == 128 else 8) == 0:
+            assert torch.equal(ca.compact_attn_forward_natural(q, k, v, lay), out)
+        assert torch.equal(ca.compact_attn_forward_static(qp, kp, vp, lay), out_tiled)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            want = OA.masked_attention(g, oracle_heads, to_f64(q[b]), to_f64(k[b]), to_f64(v[b]))
+            compare(to_f64(out[b]), want, *tolerances("bf16"), what=f"seed {seed} forward")
+            want = OA.dense_attention(to_f64(q[b]), to_f64(k[b]), to_f64(v[b]))
+            compare(to_f64(dense[b]), want, *tolerances("bf16"), what=f"seed {seed} dense")
+            for h in range(Hd):
+                want = OS.tile_mass(g, to_f64(q[b, h]), to_f64(k[b, h]))
+                assert np.abs(mass[b, h].double().cpu().numpy() - want).max() <= MASS_ABS, f"seed {seed} mass"
+        lay.free()
+
+
 # ---------------------------------------------------------------- batch > 1
 
 @pytest.mark.parametrize("dtype,D,tile", [("bf16", 128, (2, 8, 8)), ("bf16", 64, (1, 8, 8)), ("f32", 64, (1, 4, 4))])
