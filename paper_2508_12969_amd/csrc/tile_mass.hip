@@ -142,18 +142,29 @@ void tile_mass_kernel(MassArgs a) {
   const float4 inv = *reinterpret_cast<const float4*>(&lds_inv[4 * l4]);
   const float4 ref = *reinterpret_cast<const float4*>(&lds_ref[4 * l4]);
   const float c2 = w.c2;
-#pragma unroll 4
-  for (int b = sub; b < n; b += kTilesPerPass) {
-    const float4* p = reinterpret_cast<const float4*>(part + (int64_t)b * B + 4 * l4);
-    const float4 p01 = p[0], p23 = p[1];  // (e0, m0, e1, m1), (e2, m2, e3, m3)
-    const float t0 = p01.x * __builtin_amdgcn_exp2f((p01.y - ref.x) * c2) * inv.x;
-    const float t1 = p01.z * __builtin_amdgcn_exp2f((p01.w - ref.y) * c2) * inv.y;
-    const float t2 = p23.x * __builtin_amdgcn_exp2f((p23.y - ref.z) * c2) * inv.z;
-    const float t3 = p23.z * __builtin_amdgcn_exp2f((p23.w - ref.w) * c2) * inv.w;
-    float s = (t0 + t1) + (t2 + t3);
+  // kBatch key tiles per lane at a time, all loads requested before the first is used
+  constexpr int kBatch = 4;
+  for (int b0 = sub; b0 < n; b0 += kBatch * kTilesPerPass) {
+    float4 p01[kBatch], p23[kBatch];  // (e0, m0, e1, m1), (e2, m2, e3, m3)
 #pragma unroll
-    for (int sh = kLanesPerTile / 2; sh >= 1; sh >>= 1) s += __shfl_xor(s, sh, 64);
-    if (l4 == 0) out[b] = s;
+    for (int u = 0; u < kBatch; ++u) {
+      const int b = min(b0 + u * kTilesPerPass, n - 1);  // past the end: a valid tile, not stored
+      const float4* p = reinterpret_cast<const float4*>(part + (int64_t)b * B + 4 * l4);
+      p01[u] = p[0];
+      p23[u] = p[1];
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int b = b0 + u * kTilesPerPass;
+      const float t0 = p01[u].x * __builtin_amdgcn_exp2f((p01[u].y - ref.x) * c2) * inv.x;
+      const float t1 = p01[u].z * __builtin_amdgcn_exp2f((p01[u].w - ref.y) * c2) * inv.y;
+      const float t2 = p23[u].x * __builtin_amdgcn_exp2f((p23[u].y - ref.z) * c2) * inv.z;
+      const float t3 = p23[u].z * __builtin_amdgcn_exp2f((p23[u].w - ref.w) * c2) * inv.w;
+      float s = (t0 + t1) + (t2 + t3);
+#pragma unroll
+      for (int sh = kLanesPerTile / 2; sh >= 1; sh >>= 1) s += __shfl_xor(s, sh, 64);
+      if (l4 == 0 && b < n) out[b] = s;
+    }
   }
 }
 
