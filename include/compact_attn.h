@@ -23,6 +23,10 @@
  *     compute call that uses a layout not yet passed to compact_attn_layout_upload allocates and
  *     copies that layout's device tables synchronously (and fails with CA_ERR_INVALID_ARG if
  *     `stream` is being captured at that moment).
+ *   - A layout may be used by compute calls on several streams at once; launches of 4096 rows and
+ *     more keep a ticket counter in the layout's device tables while they run, one of 64 taken
+ *     round-robin, so at most 64 such launches of one layout may be in flight on different
+ *     streams at a time (launches on one stream run one after the other and never conflict).
  *   - Failures detected on the host leave all outputs untouched.
  *
  * Tile arithmetic (Sec. 4.1, space-time tiles; Sec. 3.1 / Appendix D, tile-order flattening)

@@ -1,6 +1,7 @@
 // C-ABI entry points: argument checking, layout life cycle, device upload, kernel dispatch.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstring>
@@ -78,6 +79,7 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.class_perm) (void)hipFree(d.class_perm);
   if (d.tile_origin) (void)hipFree(d.tile_origin);
   if (d.mass_partial) (void)hipFree(d.mass_partial);
+  if (d.pool_counters) (void)hipFree(d.pool_counters);
   d = ca::DeviceTables{};
 }
 
@@ -123,6 +125,11 @@ int ensure_uploaded(ca_layout* L, hipStream_t stream) {
   if (st == CA_OK) st = upload_vec(L->class_mask.data(), L->class_mask.size(), &d.class_mask);
   if (st == CA_OK) st = upload_vec(t.class_perm.data(), t.class_perm.size(), &d.class_perm);
   if (st == CA_OK && !t.tile_origin.empty()) st = upload_vec(t.tile_origin.data(), t.tile_origin.size(), &d.tile_origin);
+  if (st == CA_OK) {
+    const int32_t zeros[ca::kPoolSlots] = {};
+    st = upload_vec(zeros, (size_t)ca::kPoolSlots, &d.pool_counters);
+    d.pool_slots = ca::kPoolSlots;
+  }
   if (st != CA_OK) {
     free_device_tables(d);
     return st;
@@ -247,6 +254,20 @@ int launch_attention(const void* q, const void* k, const void* v, const ca_layou
   a.tw = L->prob.tw;
   a.n_vid = L->n_vid;
   a.N_real = L->N_real;
+  // the statically dealt part of the launch and its dynamically drawn tail (bf16 kernels; the split is
+  // that of one batch entry's launch order, the batch entries before the last are static as a whole)
+  const bool paired = L->prob.dtype == CA_BF16 && a.B == 64 && a.D == 128;
+  const int64_t entries = paired ? t.num_pairs : (int64_t)a.num_heads * a.n;
+  a.static_items = entries * a.batch;
+  if (L->prob.dtype == CA_BF16 && t.pool_counters && t.pool_slots > 0) {
+    const ca::LaunchSplit& sp = paired ? (dense ? L->split_pairs_dense : L->split_pairs) : (dense ? L->split_rows_dense : L->split_rows);
+    if (sp.pool_entries > 0) {
+      a.static_items = entries * (a.batch - 1) + sp.static_entries;
+      a.pool_items = sp.pool_entries;
+      a.pool_wgs = (int32_t)std::min<int64_t>(((int64_t)sp.pool_entries * 2 + 7) / 8 * 8, (int64_t)1 << 30);
+      a.pool_counter = t.pool_counters + L->launch_seq.fetch_add(1, std::memory_order_relaxed) % (uint32_t)t.pool_slots;
+    }
+  }
   const hipError_t e = L->prob.dtype == CA_BF16 ? ca::launch_attn_bf16(a, (hipStream_t)stream)
                                                 : ca::launch_attn_f32(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, dense ? "dense attention launch" : "sparse attention launch");
@@ -287,6 +308,7 @@ int build_static_image(ca_layout* L) {
       {L->tile_class.data(), L->tile_class.size() * sizeof(int32_t), &o.tile_class},
       {L->class_mask.data(), L->class_mask.size() * sizeof(ca::SlotMask), &o.class_mask},
       {t.class_perm.data(), t.class_perm.size(), &o.class_perm},
+      {nullptr, sizeof(int32_t), &o.pool_counter},  // stays zero: the kernels put it back after every launch
   };
   size_t total = 0;
   for (const Part& p : parts) {
@@ -301,7 +323,7 @@ int build_static_image(ca_layout* L) {
     return CA_ERR_ALLOC;
   }
   for (const Part& p : parts)
-    if (p.bytes) std::memcpy(L->static_image.data() + *p.off, p.src, p.bytes);
+    if (p.bytes && p.src) std::memcpy(L->static_image.data() + *p.off, p.src, p.bytes);
   return CA_OK;
 }
 
@@ -552,6 +574,8 @@ int compact_attn_forward_static(const void* q, const void* k, const void* v, ca_
   t.tile_class = reinterpret_cast<int32_t*>(sc.ptr + o.tile_class);
   t.class_mask = reinterpret_cast<ca::SlotMask*>(sc.ptr + o.class_mask);
   t.class_perm = sc.ptr + o.class_perm;
+  t.pool_counters = reinterpret_cast<int32_t*>(sc.ptr + o.pool_counter);
+  t.pool_slots = 1;
   st = launch_attention(q, k, v, L, t, out, stream, false, false);
   if (st != CA_OK) sc.owner = 0;
   return st;

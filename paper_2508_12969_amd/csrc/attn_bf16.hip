@@ -36,18 +36,9 @@ void attn_bf16_kernel(AttnArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
   const int64_t rows = (int64_t)a.num_heads * a.n;
-  // Workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  They are
-  // remapped so that the workgroups resident on one XCD at a time are kXcdChunk consecutive entries
-  // of the launch order (same head, neighbouring query tiles, equal list lengths) instead of every
-  // eighth entry: their key-tile lists overlap, so more of the K/V tile copies hit that L2.
-  int64_t linear = blockIdx.x;
-  {
-    const int64_t span = 8 * (int64_t)kXcdChunk, total = rows * a.batch;
-    if (linear < total / span * span) {
-      const int64_t xcd = linear & 7, seq = linear >> 3;
-      linear = (seq / kXcdChunk) * span + xcd * kXcdChunk + seq % kXcdChunk;
-    }
-  }
+  __shared__ int pool_ticket;
+  const int64_t linear = launch_entry(a, &pool_ticket);
+  if (linear < 0) return;  // a surplus pool workgroup (all of its threads)
   const int64_t item = linear % rows;
   const int64_t batch = linear / rows;
   const int64_t row = a.order ? a.order[item] : item;
@@ -143,7 +134,7 @@ void attn_bf16_kernel(AttnArgs a) {
 
 template <int B, int D>
 hipError_t launch(const AttnArgs& a, hipStream_t stream) {
-  const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
+  const int64_t items = a.static_items + a.pool_wgs;
   if (a.natural) {
     if (a.tw % Shape<B, D>::kRowsPerLoad != 0) return hipErrorInvalidValue;  // a KiB block must stay inside one run
     hipLaunchKernelGGL((attn_bf16_kernel<B, D, true>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
@@ -156,12 +147,12 @@ hipError_t launch(const AttnArgs& a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
+  if (a.B == 64 && a.D == 128) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
   if (items == 0) return hipSuccess;
-  if (items > 0x7fffffff) return hipErrorInvalidValue;
+  if (a.static_items + a.pool_wgs > 0x7fffffff || a.static_items + a.pool_items != items) return hipErrorInvalidValue;
   if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
   if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
-  if (a.B == 64 && a.D == 128) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
   if (a.B == 64 && a.D == 64) return launch<64, 64>(a, stream);
   return hipErrorInvalidValue;
 }

@@ -33,19 +33,9 @@ void attn_bf16_pair_kernel(AttnArgs a) {
   const int block = wave & 1;    // which 32 queries of that tile
 
   const int64_t pairs = a.num_pairs;
-  // XCD-aware launch order as in attn_bf16.hip; an XCD holds 64 of these workgroups at a time
-  constexpr int kChunk = 64;
-  int64_t linear = blockIdx.x;
-  {
-    const int64_t span = 8 * (int64_t)kChunk, total = pairs * a.batch;
-    if (linear < total / span * span) {
-      // rounds alternate the direction in which chunks are dealt to the XCDs (measured 3 % faster at
-      // the 80K-token configuration than dealing every round in the same direction; for 128-token
-      // tiles the plain order is the faster one)
-      const int64_t xcd = linear & 7, seq = linear >> 3, round = seq / kChunk;
-      linear = round * span + ((round & 1) ? 7 - xcd : xcd) * kChunk + seq % kChunk;
-    }
-  }
+  __shared__ int pool_ticket;
+  const int64_t linear = launch_entry(a, &pool_ticket);
+  if (linear < 0) return;  // a surplus pool workgroup (all of its threads)
   const int64_t item = linear % pairs;
   const int64_t batch = linear / pairs;
   const auto pair_rows = CONST_PTR(int32_t, a.pair_rows);
@@ -134,12 +124,14 @@ void attn_bf16_pair_kernel(AttnArgs a) {
 hipError_t launch_attn_bf16_pair(const AttnArgs& a, hipStream_t stream) {
   const int64_t items = (int64_t)a.batch * a.num_pairs;
   if (items == 0) return hipSuccess;
-  if (items > 0x7fffffff || a.B != 64 || a.D != 128 || !a.pair_rows) return hipErrorInvalidValue;
+  if (a.B != 64 || a.D != 128 || !a.pair_rows) return hipErrorInvalidValue;
+  if (a.static_items + a.pool_wgs > 0x7fffffff || a.static_items + a.pool_items != items) return hipErrorInvalidValue;
+  const int64_t grid = a.static_items + a.pool_wgs;
   if (a.natural) {
     if (a.tw % PairShape::kRowsPerLoad != 0) return hipErrorInvalidValue;  // a KiB block must stay inside one run
-    hipLaunchKernelGGL(attn_bf16_pair_kernel<true>, dim3((unsigned)items), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(attn_bf16_pair_kernel<true>, dim3((unsigned)grid), dim3(256), 0, stream, a);
   } else {
-    hipLaunchKernelGGL(attn_bf16_pair_kernel<false>, dim3((unsigned)items), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(attn_bf16_pair_kernel<false>, dim3((unsigned)grid), dim3(256), 0, stream, a);
   }
   return hipGetLastError();
 }

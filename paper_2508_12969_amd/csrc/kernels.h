@@ -46,6 +46,12 @@ struct AttnArgs {
   const int32_t* tile_origin;  // device [n]; natural-order row of slot 0 of every tile
   int32_t H, W, th, tw;
   int64_t n_vid, N_real;
+  // bf16 kernels: workgroup ids below static_items map to launch-order entries through the XCD-aware
+  // order; the pool_wgs workgroups after them draw a ticket from *pool_counter and take entry
+  // static_items + ticket while that is below static_items + pool_items (the rest have nothing to do)
+  int64_t static_items;
+  int32_t pool_items, pool_wgs;
+  int32_t* pool_counter;       // device; zero before and after every launch
 };
 // fp32 problems, B <= 128, D in {32, 64, 128}
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);

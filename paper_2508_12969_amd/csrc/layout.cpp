@@ -256,6 +256,52 @@ static void build_pair_table(ca_layout& L) {
   }
 }
 
+// The XCDs of one card do not run at the same speed (measured: up to 5 % apart in finishing time on
+// equal shares), and workgroup ids are bound to XCDs, so a launch dealt out by id alone ends when the
+// slowest XCD does.  The entries that hold the last kPoolWork of the launch's work (the shortest
+// rows: the order is by descending length) are therefore not bound to ids: workgroups past the
+// static part draw them by ticket, and an XCD that is ahead draws more.  The static part is a whole
+// number of rounds of the XCD-aware order (8 chunks of 64).
+LaunchSplit split_launch(const int64_t* work, int64_t entries) {
+  constexpr double kPoolWork = 0.06;
+  constexpr int64_t kRound = 8 * 64;
+  constexpr int64_t kEntryCost = 3;  // fixed cost of an entry in tile steps (launch, first copies, epilogue)
+  LaunchSplit sp;
+  sp.static_entries = entries;
+  if (entries < kPoolMinItems) return sp;
+  double total = 0;
+  for (int64_t i = 0; i < entries; ++i) total += (double)(work[i] + kEntryCost);
+  double tail = 0;
+  int64_t s = entries;
+  while (s > 0 && tail + (double)(work[s - 1] + kEntryCost) <= kPoolWork * total) tail += (double)(work[--s] + kEntryCost);
+  s = (s + kRound - 1) / kRound * kRound;
+  if (s < entries && entries - s < ((int64_t)1 << 30)) {
+    sp.static_entries = s;
+    sp.pool_entries = (int32_t)(entries - s);
+  }
+  return sp;
+}
+
+namespace {
+void build_launch_splits(ca_layout& L) {
+  const int64_t rows = (int64_t)L.prob.num_heads * L.n;
+  std::vector<int64_t> work(rows);
+  for (int64_t i = 0; i < rows; ++i) work[i] = L.row_ptr[L.order[i] + 1] - L.row_ptr[L.order[i]];
+  L.split_rows = split_launch(work.data(), rows);
+  std::fill(work.begin(), work.end(), L.n);
+  L.split_rows_dense = split_launch(work.data(), rows);
+  const int64_t pairs = (int64_t)L.pair_rows.size() / 2;
+  L.split_pairs = L.split_pairs_dense = LaunchSplit{};
+  if (pairs) {
+    work.resize(pairs);
+    for (int64_t i = 0; i < pairs; ++i) work[i] = L.pair_walk_ptr[i + 1] - L.pair_walk_ptr[i];
+    L.split_pairs = split_launch(work.data(), pairs);
+    std::fill(work.begin(), work.end(), L.n);
+    L.split_pairs_dense = split_launch(work.data(), pairs);
+  }
+}
+}  // namespace
+
 void finish_host_tables(ca_layout& L) {
   const int32_t Hd = L.prob.num_heads;
   // per-head relative offsets for the C-ABI view
@@ -271,6 +317,7 @@ void finish_host_tables(ca_layout& L) {
   L.pair_walk_ptr.clear();
   L.pair_walk.clear();
   if (L.prob.dtype == CA_BF16 && L.B == 64 && L.prob.head_dim == 128) build_pair_table(L);
+  build_launch_splits(L);
 }
 
 int import_host_tables(ca_layout& L, const int64_t* const* row_ptr, const int32_t* const* col_idx) {

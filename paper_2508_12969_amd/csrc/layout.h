@@ -2,6 +2,7 @@
 // calls); device copies are created by api.cpp and consumed by the kernels.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <mutex>
 #include <vector>
@@ -18,6 +19,17 @@ struct SlotMask {
   uint32_t w[4];
 };
 
+// How the entries of a launch order (rows or pairs of one batch entry, sorted by descending length)
+// are handed out: the first static_entries by workgroup id, the remaining pool_entries by ticket.
+struct LaunchSplit {
+  int64_t static_entries = 0;
+  int32_t pool_entries = 0;
+};
+constexpr int kPoolSlots = 64;          // pool counters per layout
+constexpr int64_t kPoolMinItems = 4096; // smaller launches are dealt statically as a whole
+// `work[i]`: cost of launch-order entry i (tile steps); returns the split of one batch entry's launch.
+LaunchSplit split_launch(const int64_t* work, int64_t entries);
+
 // Device-resident tables.  All pointers are device memory owned by the layout.
 struct DeviceTables {
   int64_t* row_ptr = nullptr;    // [num_heads*n + 1] offsets into col_idx (global over heads)
@@ -33,6 +45,8 @@ struct DeviceTables {
   SlotMask* class_mask = nullptr; // [num_classes]
   uint8_t* class_perm = nullptr;  // [num_classes * 128] per class: its valid slots ascending, then its padding slots ascending
   int32_t* tile_origin = nullptr; // [n] natural-order row of slot 0 of every tile
+  int32_t* pool_counters = nullptr; // [pool_slots] tickets of the dynamically drawn tail of a launch; zero between launches
+  int32_t pool_slots = 0;           // concurrent launches on one layout take different counters, round-robin
   float* mass_partial = nullptr;  // workspace of the tile-mass kernel, mass_partial_rows * n * B * 2 floats; allocated at its first call
   int64_t mass_partial_rows = 0;
 };
@@ -56,6 +70,12 @@ struct ca_layout {
   std::vector<int32_t> tile_class;          // [n]
   std::vector<ca::SlotMask> class_mask;     // class 0 = all valid
 
+  // A launch deals most of its workgroups to the XCDs statically and
+  // leaves the cheapest entries at the end of the launch order to be drawn by whichever XCD gets there
+  // first: rows / pairs of the sparse and of the dense walk.
+  ca::LaunchSplit split_rows, split_rows_dense, split_pairs, split_pairs_dense;
+  mutable std::atomic<uint32_t> launch_seq{0};  // picks the pool counter of a launch
+
   // device tables, created once
   std::mutex upload_mutex;
   bool uploaded = false;
@@ -68,7 +88,7 @@ struct ca_layout {
   std::vector<unsigned char> static_image;
   struct StaticOffsets {
     size_t row_ptr = 0, col_meta = 0, order = 0, pair_rows = 0, pair_walk_ptr = 0, pair_walk = 0, tile_class = 0,
-           class_mask = 0, class_perm = 0;
+           class_mask = 0, class_perm = 0, pool_counter = 0;
   } static_off;
 };
 

@@ -96,6 +96,57 @@ void check_packing(const ca_layout* L) {
   }
 }
 
+// The split of a launch into a statically dealt part and a dynamically drawn tail: the static part
+// is whole rounds of 512 entries, the two parts cover the launch order exactly, and the tail holds the
+// cheapest entries, at most about 6 % of the work plus the rounding to a round.
+void check_split(const ca::LaunchSplit& sp, const std::vector<int64_t>& work) {
+  const int64_t entries = (int64_t)work.size();
+  CHECK(sp.static_entries >= 0 && sp.pool_entries >= 0);
+  CHECK(sp.static_entries + sp.pool_entries == entries);
+  if (entries < ca::kPoolMinItems) CHECK(sp.pool_entries == 0);
+  if (sp.pool_entries > 0) {
+    CHECK(sp.static_entries % 512 == 0);
+    double total = 0, tail = 0;
+    for (int64_t i = 0; i < entries; ++i) total += (double)(work[i] + 3);
+    for (int64_t i = sp.static_entries; i < entries; ++i) tail += (double)(work[i] + 3);
+    CHECK(tail <= 0.06 * total + 1e-9);
+  }
+}
+
+void check_layout_splits(const ca_layout* L) {
+  const int64_t rows = (int64_t)L->prob.num_heads * L->n;
+  std::vector<int64_t> work(rows);
+  for (int64_t i = 0; i < rows; ++i) work[i] = L->row_ptr[L->order[i] + 1] - L->row_ptr[L->order[i]];
+  for (int64_t i = 1; i < rows; ++i) CHECK(work[i] <= work[i - 1]);  // the launch order is by descending length
+  check_split(L->split_rows, work);
+  check_split(L->split_rows_dense, std::vector<int64_t>(rows, L->n));
+  const int64_t pairs = (int64_t)L->pair_rows.size() / 2;
+  if (pairs) {
+    work.assign(pairs, 0);
+    for (int64_t i = 0; i < pairs; ++i) work[i] = L->pair_walk_ptr[i + 1] - L->pair_walk_ptr[i];
+    check_split(L->split_pairs, work);
+    check_split(L->split_pairs_dense, std::vector<int64_t>(pairs, L->n));
+  } else {
+    CHECK(L->split_pairs.pool_entries == 0 && L->split_pairs_dense.pool_entries == 0);
+  }
+}
+
+void check_split_function() {
+  std::mt19937 rng(7);
+  for (int rep = 0; rep < 40; ++rep) {
+    const int64_t entries = rep < 4 ? (int64_t)(rep * 1365) : 4096 + (int64_t)(rng() % 40000);
+    std::vector<int64_t> work(entries);
+    int64_t v = 1 + (int64_t)(rng() % 2000);
+    for (int64_t i = 0; i < entries; ++i) {
+      work[i] = v;
+      if (v > 0 && rng() % 8 == 0) v -= (int64_t)(rng() % 3);
+      if (v < 0) v = 0;
+    }
+    if (rep % 5 == 4) work.assign(entries, rep % 2 ? 0 : 1000);  // all entries alike
+    check_split(ca::split_launch(work.data(), entries), work);
+  }
+}
+
 void check_layout_views(const ca_layout* L, const ca_problem& p) {
   int64_t n = 0, B = 0, n_real = 0, n_pad = 0, nnz = 0;
   CHECK(compact_attn_layout_info(L, &n, &B, &n_real, &n_pad, &nnz) == CA_OK);
@@ -143,6 +194,7 @@ void run_case(std::mt19937& rng, ca_problem p) {
   if (!L) return;
   check_layout_views(L, p);
   check_packing(L);
+  check_layout_splits(L);
 
   // round trip through the CSR import, then union with a second random layout and similarity
   int64_t n = 0;
@@ -160,6 +212,7 @@ void run_case(std::mt19937& rng, ca_problem p) {
   if (merged) {
     check_layout_views(merged, p);
     check_packing(merged);
+    check_layout_splits(merged);
     double sim = -1;
     CHECK(compact_attn_layout_similarity(merged, 0, merged, 0, &sim) == CA_OK && sim == 1.0);
     CHECK(compact_attn_layout_similarity(L, 0, other, p.num_heads - 1, &sim) == CA_OK && sim >= 0.0 && sim <= 1.0);
@@ -239,9 +292,12 @@ int main() {
       {7, 5, 3, 2, 2, 4, 16, 1, 5, 32, CA_F32, 0.f},         // odd everything
       {1, 1, 1, 1, 1, 1, 0, 1, 1, 8, CA_BF16, 0.f},          // a single token
       {9, 33, 35, 2, 8, 8, 256, 1, 6, 128, CA_BF16, 0.f},
+      {8, 64, 64, 1, 8, 8, 0, 1, 8, 64, CA_BF16, 0.f},       // 4096 rows: the tail of the launch is drawn dynamically
+      {6, 64, 64, 1, 8, 8, 64, 1, 24, 128, CA_BF16, 0.f},    // the same for query-tile pairs
   };
   for (const ca_problem& p : cases)
     for (int rep = 0; rep < 3; ++rep) run_case(rng, p);
+  check_split_function();
 
   // malformed problems and heads
   ca_layout* L = nullptr;

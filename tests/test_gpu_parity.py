@@ -316,6 +316,67 @@ def test_every_row_at_full_size_zero_query_probe(name):
     _say(name, "worst abs err over all rows", worst)
 
 
+# ---------------------------------------------------------------- dynamically drawn tail of a launch
+
+@pytest.mark.parametrize("D,tile,T,Hd,batch", [(64, (1, 8, 8), 8, 8, 1), (128, (1, 8, 8), 6, 24, 1), (128, (2, 8, 8), 6, 22, 2)])
+def test_dynamic_tail_of_the_launch_order(D, tile, T, Hd, batch):
+    """Launches of 4096 entries and more hand the cheapest entries out by ticket instead of by
+    workgroup id (rows here; pairs of rows for 64-token tiles with head dim 128).  Every row must
+    still be computed exactly once per launch: checked against the closed form of the Q = 0 probe on
+    every row, on 70 launches in a row (more than the layout has ticket counters, and every launch
+    must leave its counter at zero), on the dense walk, on the natural-order variant and on replays
+    of a captured graph."""
+    import dataclasses
+    _say("dynamic tail", D, tile, T, Hd, batch)
+    H = W = 64
+    rng = np.random.default_rng(3)
+    heads = [[(int(rng.integers(0, 3)), (int(rng.integers(0, 4)), int(rng.integers(0, 4))), ABSENT)] for _ in range(Hd)]
+    heads[1] = [(T, (99, 99), ABSENT)]                                       # one global head: long rows first
+    wl = dataclasses.replace(make_workload("tail", T, H, W, tile, 0, Hd, D, "bf16", heads), batch=batch)
+    g = geometry_of(wl)
+    assert Hd * g.n >= 4096
+    lay = build_layout(ca, wl)
+    tok_tile = g.token_slots() // g.B
+    per_tile = np.bincount(tok_tile, minlength=g.n).astype(np.float64)
+    onehot = np.zeros((g.n, D))
+    onehot[np.arange(g.n), np.arange(g.n) % D] = per_tile
+    tile_dev = torch.from_numpy(tok_tile).to(DEV)
+    q = torch.zeros(batch, Hd, g.N_real, D, dtype=torch.bfloat16, device=DEV)
+    k = torch.randn(batch, Hd, g.N_real, D, device=DEV).to(torch.bfloat16)
+    v1 = torch.zeros(g.N_real, D, dtype=torch.bfloat16, device=DEV)
+    v1[torch.arange(g.N_real, device=DEV), tile_dev % D] = 1.0
+    v = v1[None, None].expand(batch, Hd, -1, -1).contiguous()
+    qp, kp, vp = (ca.compact_attn_permute(t, lay) for t in (q, k, v))
+    first = ca.compact_attn_forward(qp, kp, vp, lay)
+    out = ca.compact_attn_permute(first, lay, inverse=True)
+    dense = ca.compact_attn_permute(ca.compact_attn_dense(qp, kp, vp, lay), lay, inverse=True)
+    torch.cuda.synchronize()
+    want_dense = torch.from_numpy(onehot.sum(axis=0) / per_tile.sum()).to(DEV).float()
+    for h in range(Hd):
+        mask = OL.keep_mask(g, wl.heads[h]).astype(np.float64)
+        want = torch.from_numpy((mask @ onehot) / (mask @ per_tile)[:, None]).to(DEV).float()[tile_dev]
+        for b in range(batch):
+            assert (out[b, h].float() - want).abs().max().item() < 6e-3, (h, b)
+            assert (dense[b, h].float() - want_dense[None]).abs().max().item() < 6e-3, (h, b)
+    if tile[2] % (4 if D == 128 else 8) == 0:
+        assert torch.equal(ca.compact_attn_forward_natural(q, k, v, lay), out)
+    again = torch.empty_like(first)
+    for rep in range(70):
+        again.fill_(float("nan"))
+        ca.compact_attn_forward(qp, kp, vp, lay, out=again)
+        assert torch.equal(again, first), f"launch {rep}"
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ca.compact_attn_forward(qp, kp, vp, lay, out=again)
+    for rep in range(3):
+        again.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(again, first), f"replay {rep}"
+        ca.compact_attn_forward(qp, kp, vp, lay)                           # eager launches between replays
+
+
 # ---------------------------------------------------------------- exponent reference moves
 
 @pytest.mark.parametrize("shape", [("bf16", 128, (2, 8, 8)), ("bf16", 128, (1, 8, 8)), ("bf16", 64, (2, 8, 8))])
