@@ -238,8 +238,9 @@ int compact_attn_dense(const void* q, const void* k, const void* v, ca_layout* l
  * Row a of mass sums to the number of real tokens of tile a.  One Q K^T product per tile pair: half
  * the FLOPs of one dense pass.
  *   Workspace: the kernel keeps two floats per (query token, key tile) of the rows in flight.  The
- *   first call for a layout allocates min(batch * heads * n, 1024) * N_pad * 8 bytes of device
- *   memory (synchronously; refused with CA_ERR_INVALID_ARG on a stream under capture: call once
+ *   first call for a layout allocates min(batch * heads * n, W) * N_pad * 8 bytes of device memory,
+ *   W = the workgroups the device holds at a time (two per compute unit for 128-token tiles, four
+ *   for 64-token tiles: 0.54 GB for 130K tokens on 256 compute units), (synchronously; refused with CA_ERR_INVALID_ARG on a stream under capture: call once
  *   before capturing), which the layout owns until compact_attn_free_layout.  Calls on the same
  *   layout that overlap in time (different streams) would share that workspace and race: give
  *   concurrent calls a layout each.  CA_ERR_ALLOC if the allocation fails.

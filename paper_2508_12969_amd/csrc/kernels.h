@@ -64,9 +64,11 @@ struct MassArgs {
   const void* q;               // [batch, heads, N_pad, D] tile order, bf16
   const void* k;
   float* mass;                 // [batch, heads, n, n]
-  float* partial;              // device workspace, partial_rows * n * B * 2 floats: per query and key tile (sum, reference) of the rows of one launch
-  int64_t partial_rows;        // rows (workgroups) per launch
-  int64_t row_base;            // first row of the launch (set by the launcher)
+  float* partial;              // device workspace, partial_rows * n * B * 2 floats: per query and key tile (sum, reference) of the row a workgroup is working on
+  int64_t partial_rows;        // blocks of the workspace = most workgroups a launch may have
+  int64_t rows_per_launch;     // rows one launch covers (all of them, or a multiple of partial_rows)
+  int64_t row_base, row_count; // set by the launcher: the rows of one launch, drawn by ticket
+  int32_t* counter;            // device; the ticket counter, zero before and after every launch
   const int32_t* dense_meta;   // device [n + 2]; per key tile: tile id | padding class << 24 | bit 31: upper key blocks empty
   const int32_t* tile_class;   // device [n]
   const SlotMask* class_mask;  // device

@@ -47,8 +47,9 @@ struct DeviceTables {
   int32_t* tile_origin = nullptr; // [n] natural-order row of slot 0 of every tile
   int32_t* pool_counters = nullptr; // [pool_slots] tickets of the dynamically drawn tail of a launch; zero between launches
   int32_t pool_slots = 0;           // concurrent launches on one layout take different counters, round-robin
-  float* mass_partial = nullptr;  // workspace of the tile-mass kernel, mass_partial_rows * n * B * 2 floats; allocated at its first call
+  float* mass_partial = nullptr;  // workspace of the tile-mass kernel, mass_partial_rows (= workgroups of its launch) * n * B * 2 floats; allocated at its first call
   int64_t mass_partial_rows = 0;
+  int32_t* mass_counter = nullptr; // its ticket counter (inside the same allocation)
 };
 
 }  // namespace ca

@@ -17,6 +17,8 @@
 //     mass[a, b] = sum_i e[b][i] * exp2(scale' * (m[b][i] - m_i)) / l_i,
 // in a fixed order, so the result is run-to-run identical.  (The alternative without a workspace
 // walks every row twice and multiplies twice; it measured twice the time per product.)
+#include <algorithm>
+
 #include "attn_bf16_common.h"
 
 namespace ca {
@@ -31,24 +33,41 @@ void tile_mass_kernel(MassArgs a) {
   __shared__ __attribute__((aligned(1024))) char lds_k[2 * S::kTileBytes];
   __shared__ __attribute__((aligned(16))) float lds_inv[B];  // 1 / l_i
   __shared__ __attribute__((aligned(16))) float lds_ref[B];  // m_i
+  __shared__ int lds_ticket;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
   const int64_t rows = (int64_t)a.num_heads * a.n;
-  const int64_t item = a.row_base + blockIdx.x;  // (batch, head, query tile), row-major
+  const int total = (int)a.row_count;  // rows of this launch: items row_base .. row_base + row_count - 1
+  // this workgroup's block of the workspace: [n][B] pairs (sum, reference), reused row after row
+  float2* part = reinterpret_cast<float2*>(a.partial) + (int64_t)blockIdx.x * a.n * B;
+  // one packed word per key tile 0..n-1: tile id | padding class << 24 | bit 31: upper key blocks empty
+  const auto meta = CONST_PTR(int32_t, a.dense_meta);
+  const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
+  const int n = (int)a.n;
+  const TileLoader<S, false> k_loader(wave, lane);
+  const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_k;
+  const LdsTile k_tile = (LdsTile)lds_k;
+
+  // The grid is at most as many workgroups as the card holds at a time; each takes (batch, head,
+  // query tile) rows of the launch by ticket until none is left, so an XCD that runs faster takes
+  // more rows.  Every workgroup draws once more than it has rows; whoever draws the last ticket of
+  // all zeroes the counter for the next launch.
+  for (;;) {
+  if (threadIdx.x == 0) {
+    const int t = atomicAdd(a.counter, 1);
+    if (t == total + (int)gridDim.x - 1) __hip_atomic_store(a.counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    lds_ticket = t;
+  }
+  __syncthreads();
+  if (lds_ticket >= total) return;  // all threads of the workgroup alike
+  const int64_t item = a.row_base + lds_ticket;  // (batch, head, query tile), row-major
   const int64_t row = item % rows;
   const int64_t batch = item / rows;
   const int64_t head = row / a.n, q_tile = row - head * a.n;
   const int64_t plane = (batch * a.num_heads + head) * a.n * (int64_t)S::kTileBytes;
   const char* Kp = static_cast<const char*>(a.k) + plane;
   float* out = a.mass + item * a.n;
-  // this workgroup's block of the workspace: [n][B] pairs (sum, reference)
-  float2* part = reinterpret_cast<float2*>(a.partial) + (int64_t)blockIdx.x * a.n * B;
-  // one packed word per key tile 0..n-1: tile id | padding class << 24 | bit 31: upper key blocks empty
-  const auto meta = CONST_PTR(int32_t, a.dense_meta);
-  const auto class_mask = CONST_PTR(uint32_t, a.class_mask);  // 4 words per class
-  const int n = (int)a.n;
 
   // A wave without a real query (see query_slot) takes part in the tile copies and barriers only.
   QueryWave<S> w(lane, a.scale);
@@ -57,10 +76,6 @@ void tile_mass_kernel(MassArgs a) {
   w.load_q(static_cast<const char*>(a.q) + plane + (q_tile * B + qs.slot) * S::kRowBytes);
   const int mine = wave * 32 + w.qi;  // this lane's query in the workspace block and in lds_inv
   const bool writer = w.g == 0;       // both lanes of a pair hold the query's sum; the lower one stores it
-
-  const TileLoader<S, false> k_loader(wave, lane);
-  const uint32_t lds_k_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_k;
-  const LdsTile k_tile = (LdsTile)lds_k;
 
   // the packed words are fetched two steps ahead of their use (the table is readable two words past its end)
   int32_t word = meta[0], word1 = meta[1];
@@ -166,17 +181,19 @@ void tile_mass_kernel(MassArgs a) {
       if (l4 == 0 && b < n) out[b] = s;
     }
   }
+  __syncthreads();  // the row is done: its ticket and its LDS tables may be overwritten
+  }
 }
 
 template <int B, int D>
 hipError_t launch(MassArgs a, hipStream_t stream) {
-  // The workspace holds a.partial_rows workgroups; launches on one stream run one after another, so
-  // each can use it from the start.
+  // Launches on one stream run one after another, so each has the workspace and the counter to itself.
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
-  for (int64_t base = 0; base < items; base += a.partial_rows) {
-    const int64_t count = items - base < a.partial_rows ? items - base : a.partial_rows;
+  for (int64_t base = 0; base < items; base += a.rows_per_launch) {
     a.row_base = base;
-    hipLaunchKernelGGL((tile_mass_kernel<B, D>), dim3((unsigned)count), dim3(B * 2), 0, stream, a);
+    a.row_count = std::min(items - base, a.rows_per_launch);
+    const int64_t grid = std::min(a.row_count, a.partial_rows);
+    hipLaunchKernelGGL((tile_mass_kernel<B, D>), dim3((unsigned)grid), dim3(B * 2), 0, stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -188,7 +205,8 @@ hipError_t launch(MassArgs a, hipStream_t stream) {
 hipError_t launch_tile_mass(const MassArgs& a, hipStream_t stream) {
   const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
   if (items == 0) return hipSuccess;
-  if (!a.partial || a.partial_rows < 1 || a.partial_rows > 0x7fffffff) return hipErrorInvalidValue;
+  if (!a.partial || !a.counter || a.partial_rows < 1 || a.rows_per_launch < 1) return hipErrorInvalidValue;
+  if (std::min(items, a.rows_per_launch) + a.partial_rows > 0x7fffffff) return hipErrorInvalidValue;
   if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
   if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
   if (a.B == 64 && a.D == 128) return launch<64, 128>(a, stream);

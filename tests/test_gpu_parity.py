@@ -508,13 +508,14 @@ def test_tile_mass_with_a_moving_exponent_reference(shape):
             assert err.max() <= MASS_ABS
 
 
-def test_tile_mass_over_several_launches():
-    """More (batch, head, query tile) rows than one launch of the kernel covers (1024), with a ragged
-    last launch: every launch reuses the same workspace; rows on both sides of each boundary and in
-    the last launch are compared with the definition, all rows with their closed-form sums."""
+def test_tile_mass_with_more_rows_than_workgroups():
+    """More (batch, head, query tile) rows than the launch has workgroups (the device holds 1024 of
+    this shape at a time), so workgroups take a second row by ticket and reuse their block of the
+    workspace: rows of both batch entries are compared with the definition, all rows with their
+    closed-form sums."""
     import dataclasses
     from oracle import search as OS
-    _say("tile mass, several launches")
+    _say("tile mass, more rows than workgroups")
     T, H, W, tile, D, Hd, batch = 6, 32, 32, (1, 8, 8), 64, 6, 2
     wl = dataclasses.replace(make_workload("masslaunch", T, H, W, tile, 0, Hd, D, "bf16", [[]] * Hd), batch=batch)
     g = geometry_of(wl)
