@@ -365,6 +365,14 @@ def test_dynamic_tail_of_the_launch_order(D, tile, T, Hd, batch):
         again.fill_(float("nan"))
         ca.compact_attn_forward(qp, kp, vp, lay, out=again)
         assert torch.equal(again, first), f"launch {rep}"
+    for rep in range(3):                                                    # the allocation-free entry point keeps
+        again.fill_(float("nan"))                                          # its one ticket counter in the fixed array
+        try:
+            ca.compact_attn_forward_static(qp, kp, vp, lay, out=again)
+        except ca.CompactAttnError as exc:
+            assert exc.status == -2                                         # tables beyond the array: refused, fine
+            break
+        assert torch.equal(again, first), f"static launch {rep}"
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         ca.compact_attn_forward(qp, kp, vp, lay, out=again)
