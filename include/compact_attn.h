@@ -147,20 +147,39 @@ int compact_attn_layout_csr(const ca_layout* layout, int32_t head, const int64_t
 /* Host view of the launch order: int32[num_heads*n] of row ids head*n + query_tile. */
 int compact_attn_layout_order(const ca_layout* layout, const int32_t** order);
 
-/* Host view of the query-tile pairs (work ordering of Appendix D's block loop when a workgroup owns
- * two query tiles and walks the union of their kept lists, used for bf16, 64-token tiles, head_dim
- * 128): *pairs -> int32[2 * *num_pairs]; entries 2i and 2i+1 are row ids head*n + query_tile of the
- * two tiles of pair i (same head, neighbours along one grid axis chosen per head so that the unions
- * are smallest; text tiles pair in id order), the second -1 when a tile has no partner.  Every row
- * of the layout is in exactly one pair.  Pairs are in launch order: descending union size, ties in
- * the order (head, first tile id).
- *   *walk_ptr -> int64[*num_pairs + 1] offsets into *walk;  *walk -> int32 words, for pair i the
+/* Host view of the workgroups that serve two query tiles (work ordering of Appendix D's block loop
+ * when a workgroup walks the union of two kept lists; bf16, head_dim 128):
+ *   *pairs -> int32[2 * *num_pairs]; entries 2i and 2i+1 are row ids head*n + query_tile of the two
+ *   tiles of workgroup i (same head), the second -1 when there is only one.
+ *   64-token tiles: every row of the layout is in exactly one pair: neighbours along one grid axis
+ *   chosen per head so that the unions are smallest; text tiles pair in id order.
+ *   128-token tiles: only query tiles on a padded face of the grid, whose tokens fill fewer than four
+ *   32-query waves, are here: their waves are packed along w, four to a workgroup, so a tile may
+ *   appear in two consecutive workgroups with different waves (compact_attn_layout_packing), and only
+ *   in heads where packing is cheaper than a workgroup per tile.
+ *   Workgroups are in launch order: descending union size, ties in the order (head, first tile id).
+ *   *walk_ptr -> int64[*num_pairs + 1] offsets into *walk;  *walk -> int32 words, for workgroup i the
  *   union of its two rows in ascending key-tile order, each word = tile id (bits 0-23)
  *   | 1 << 30 if the first tile's row keeps it | 1 << 31 if the second tile's row keeps it.
- * walk_ptr and walk may be NULL.  *num_pairs is 0 for layouts the paired kernel does not serve.
+ * walk_ptr and walk may be NULL.  *num_pairs is 0 for layouts without such workgroups.
  * Owned by the layout, valid until it is freed. */
 int compact_attn_layout_pairs(const ca_layout* layout, const int32_t** pairs, int64_t* num_pairs,
                               const int64_t** walk_ptr, const int32_t** walk);
+
+/* Host view of how the launch is divided between the kernels:
+ *   *desc -> int32[num_pairs] (num_pairs of compact_attn_layout_pairs), one word per workgroup of two
+ *   query tiles: bit w (w = 0..3): wave w works for the second tile (else the first); bit 4 + w: wave
+ *   w has queries at all; bits 8 + 4w .. 11 + 4w: the first of the wave's 32 query slots, divided by
+ *   32, in the order that lists a tile's token-holding slots first.
+ *   *launch_rows -> int32[*num_launch_rows]: the launch order of the kernel that gives a row a
+ *   workgroup of its own, longest list first: an entry >= 0 is a row id head*n + query_tile (these
+ *   are compact_attn_layout_order without the rows of packed tiles, in the same order), an entry
+ *   e < 0 stands for workgroup ~e of compact_attn_layout_pairs, which the same launch runs (128-token
+ *   tiles).  *num_launch_rows is 0 (and *launch_rows NULL) when every row is in a pair (64-token tiles).
+ * Every query slot that holds a token belongs to exactly one wave of one workgroup.  Owned by the
+ * layout, valid until it is freed. */
+int compact_attn_layout_packing(const ca_layout* layout, const int32_t** desc, const int32_t** launch_rows,
+                                int64_t* num_launch_rows);
 
 /* Copy the layout's device-side tables (CSR, order, padding masks) to the current HIP device.
  * Synchronous; idempotent.  The compute calls below do it on first use if it was not called

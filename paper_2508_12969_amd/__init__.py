@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     compact_attn_layout_info,
     compact_attn_layout_order,
     compact_attn_layout_pairs,
+    compact_attn_layout_packing,
     compact_attn_layout_similarity,
     compact_attn_layout_union,
     compact_attn_layout_upload,

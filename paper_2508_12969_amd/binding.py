@@ -31,6 +31,7 @@ EXPORTED = (
     "compact_attn_layout_csr",
     "compact_attn_layout_order",
     "compact_attn_layout_pairs",
+    "compact_attn_layout_packing",
     "compact_attn_layout_upload",
     "compact_attn_free_layout",
     "compact_attn_permute",
@@ -102,6 +103,8 @@ def load_library():
     lib.compact_attn_layout_order.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
     lib.compact_attn_layout_pairs.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)), i64p, ctypes.POINTER(i64p),
                                               ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))]
+    lib.compact_attn_layout_packing.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)),
+                                                ctypes.POINTER(ctypes.POINTER(ctypes.c_int32)), i64p]
     lib.compact_attn_layout_upload.argtypes = [vp]
     lib.compact_attn_free_layout.argtypes = [vp]
     lib.compact_attn_free_layout.restype = None
@@ -249,6 +252,19 @@ def compact_attn_layout_pairs(layout):
     total = int(walk_ptr[-1])
     walk = np.ctypeslib.as_array(w, shape=(total,)).copy() if total else np.zeros(0, dtype=np.int32)
     return pairs, walk_ptr, walk
+
+
+def compact_attn_layout_packing(layout):
+    """(desc uint32 [num_pairs]: wave assignment of every two-tile workgroup; launch_rows int32: launch order of the
+    one-row-per-workgroup kernel: row ids, and ~i for two-tile workgroup i run by the same launch)."""
+    d = ctypes.POINTER(ctypes.c_int32)()
+    r = ctypes.POINTER(ctypes.c_int32)()
+    count = ctypes.c_int64(0)
+    _check(load_library().compact_attn_layout_packing(layout.handle, ctypes.byref(d), ctypes.byref(r), ctypes.byref(count)))
+    num_pairs = compact_attn_layout_pairs(layout)[0].shape[0]
+    desc = np.ctypeslib.as_array(d, shape=(num_pairs,)).copy().view(np.uint32) if num_pairs else np.zeros(0, dtype=np.uint32)
+    rows = np.ctypeslib.as_array(r, shape=(count.value,)).copy() if count.value else np.zeros(0, dtype=np.int32)
+    return desc, rows
 
 
 def compact_attn_layout_upload(layout):

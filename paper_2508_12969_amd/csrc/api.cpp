@@ -71,6 +71,8 @@ void free_device_tables(ca::DeviceTables& d) {
   if (d.dense_meta) (void)hipFree(d.dense_meta);
   if (d.order) (void)hipFree(d.order);
   if (d.pair_rows) (void)hipFree(d.pair_rows);
+  if (d.pair_desc) (void)hipFree(d.pair_desc);
+  if (d.launch_rows) (void)hipFree(d.launch_rows);
   if (d.pair_walk_ptr) (void)hipFree(d.pair_walk_ptr);
   if (d.pair_walk) (void)hipFree(d.pair_walk);
   if (d.dense_pair_walk) (void)hipFree(d.dense_pair_walk);
@@ -118,6 +120,11 @@ int ensure_uploaded(ca_layout* L, hipStream_t stream) {
   if (st == CA_OK) st = upload_vec(L->order.data(), L->order.size(), &d.order);
   if (st == CA_OK) st = upload_vec(L->pair_rows.data(), L->pair_rows.size(), &d.pair_rows);
   d.num_pairs = (int64_t)L->pair_rows.size() / 2;
+  if (st == CA_OK && d.num_pairs) st = upload_vec(L->pair_desc.data(), L->pair_desc.size(), &d.pair_desc);
+  if (st == CA_OK && L->packed_faces) {
+    st = upload_vec(L->launch_rows.data(), L->launch_rows.size(), &d.launch_rows);
+    d.num_launch_rows = (int64_t)L->launch_rows.size();
+  }
   if (st == CA_OK && d.num_pairs) st = upload_vec(L->pair_walk_ptr.data(), L->pair_walk_ptr.size(), &d.pair_walk_ptr);
   if (st == CA_OK && d.num_pairs) st = upload_vec(t.pair_walk.data(), t.pair_walk.size(), &d.pair_walk);
   if (st == CA_OK && d.num_pairs) st = upload_vec(t.dense_pair_walk.data(), t.dense_pair_walk.size(), &d.dense_pair_walk);
@@ -244,9 +251,9 @@ int launch_attention(const void* q, const void* k, const void* v, const ca_layou
   a.out = out;
   a.row_ptr = dense ? nullptr : t.row_ptr;
   a.col_meta = dense ? t.dense_meta : t.col_meta;
-  a.order = dense ? nullptr : t.order;
   a.pair_rows = t.pair_rows;
   a.num_pairs = t.num_pairs;
+  a.pair_desc = t.pair_desc;
   a.pair_walk_ptr = dense ? nullptr : t.pair_walk_ptr;
   a.pair_walk = dense ? t.dense_pair_walk : t.pair_walk;
   a.tile_class = t.tile_class;
@@ -266,22 +273,41 @@ int launch_attention(const void* q, const void* k, const void* v, const ca_layou
   a.tw = L->prob.tw;
   a.n_vid = L->n_vid;
   a.N_real = L->N_real;
-  // the statically dealt part of the launch and its dynamically drawn tail (bf16 kernels; the split is
+  const bool bf16 = L->prob.dtype == CA_BF16;
+  // Which kernel serves which rows.  64-token tiles with head dim 128: the paired kernel, all rows.
+  // 128-token tiles with head dim 128 on a padded grid: one launch of the one-tile-per-workgroup
+  // kernel whose order (launch_rows) also holds the workgroups of packed query tiles.  Everything
+  // else: that kernel on `order`.
+  const bool all_paired = bf16 && a.B == 64 && a.D == 128;
+  const bool some_paired = bf16 && a.B == 128 && a.D == 128 && t.num_pairs > 0 && t.launch_rows;
+  a.order = some_paired ? t.launch_rows : (dense ? nullptr : t.order);
+  a.entries = some_paired ? t.num_launch_rows : (int64_t)a.num_heads * a.n;
+  a.packed = some_paired ? 1 : 0;
+  if (a.B == 128)
+    for (size_t c = 0; c < L->class_mask.size() && c < 64; ++c)
+      if ((L->class_mask[c].w[2] | L->class_mask[c].w[3]) == 0) a.upper_empty_classes |= (uint64_t)1 << c;
+  // the statically dealt part of a launch and its dynamically drawn tail (bf16 kernels; the split is
   // that of one batch entry's launch order, the batch entries before the last are static as a whole)
-  const bool paired = L->prob.dtype == CA_BF16 && a.B == 64 && a.D == 128;
-  const int64_t entries = paired ? t.num_pairs : (int64_t)a.num_heads * a.n;
-  a.static_items = entries * a.batch;
-  if (L->prob.dtype == CA_BF16 && t.pool_counters && t.pool_slots > 0) {
-    const ca::LaunchSplit& sp = paired ? (dense ? L->split_pairs_dense : L->split_pairs) : (dense ? L->split_rows_dense : L->split_rows);
-    if (sp.pool_entries > 0) {
+  auto set_split = [&](int64_t entries, const ca::LaunchSplit& sp) {
+    a.static_items = entries * a.batch;
+    a.pool_items = a.pool_wgs = 0;
+    a.pool_counter = nullptr;
+    if (bf16 && t.pool_counters && t.pool_slots > 0 && sp.pool_entries > 0) {
       a.static_items = entries * (a.batch - 1) + sp.static_entries;
       a.pool_items = sp.pool_entries;
       a.pool_wgs = (int32_t)std::min<int64_t>(((int64_t)sp.pool_entries * 2 + 7) / 8 * 8, (int64_t)1 << 30);
       a.pool_counter = t.pool_counters + L->launch_seq.fetch_add(1, std::memory_order_relaxed) % (uint32_t)t.pool_slots;
     }
+  };
+  hipError_t e = hipSuccess;
+  if (!all_paired && a.entries > 0) {
+    set_split(a.entries, dense ? L->split_rows_dense : L->split_rows);
+    e = bf16 ? ca::launch_attn_bf16(a, (hipStream_t)stream) : ca::launch_attn_f32(a, (hipStream_t)stream);
   }
-  const hipError_t e = L->prob.dtype == CA_BF16 ? ca::launch_attn_bf16(a, (hipStream_t)stream)
-                                                : ca::launch_attn_f32(a, (hipStream_t)stream);
+  if (e == hipSuccess && all_paired) {
+    set_split(t.num_pairs, dense ? L->split_pairs_dense : L->split_pairs);
+    e = ca::launch_attn_bf16_pair(a, (hipStream_t)stream);
+  }
   if (e != hipSuccess) return hip_fail(e, dense ? "dense attention launch" : "sparse attention launch");
   return CA_OK;
 }
@@ -320,7 +346,9 @@ int build_static_image(ca_layout* L) {
       {L->tile_class.data(), L->tile_class.size() * sizeof(int32_t), &o.tile_class},
       {L->class_mask.data(), L->class_mask.size() * sizeof(ca::SlotMask), &o.class_mask},
       {t.class_perm.data(), t.class_perm.size(), &o.class_perm},
-      {nullptr, sizeof(int32_t), &o.pool_counter},  // stays zero: the kernels put it back after every launch
+      {nullptr, 2 * 256, &o.pool_counter},  // two ticket counters, 256 bytes apart; they stay zero: the kernels put them back after every launch
+      {L->pair_desc.data(), paired ? L->pair_desc.size() * sizeof(int32_t) : 0, &o.pair_desc},
+      {L->launch_rows.data(), L->packed_faces ? L->launch_rows.size() * sizeof(int32_t) : 0, &o.launch_rows},
   };
   size_t total = 0;
   for (const Part& p : parts) {
@@ -483,6 +511,17 @@ int compact_attn_layout_pairs(const ca_layout* L, const int32_t** pairs, int64_t
   return CA_OK;
 }
 
+int compact_attn_layout_packing(const ca_layout* L, const int32_t** desc, const int32_t** launch_rows, int64_t* num_launch_rows) {
+  ca::clear_error();
+  if (!L || !desc || !launch_rows || !num_launch_rows) return fail(CA_ERR_INVALID_ARG, "null argument");
+  *desc = L->pair_desc.data();
+  const std::vector<int32_t>& rows = L->packed_faces ? L->launch_rows : L->order;
+  const bool all_paired = !L->pair_rows.empty() && !L->packed_faces;
+  *launch_rows = all_paired ? nullptr : rows.data();
+  *num_launch_rows = all_paired ? 0 : (int64_t)rows.size();
+  return CA_OK;
+}
+
 int compact_attn_layout_upload(ca_layout* L) {
   ca::clear_error();
   if (!L) return fail(CA_ERR_INVALID_ARG, "null layout");
@@ -588,6 +627,11 @@ int compact_attn_forward_static(const void* q, const void* k, const void* v, ca_
   t.class_perm = sc.ptr + o.class_perm;
   t.pool_counters = reinterpret_cast<int32_t*>(sc.ptr + o.pool_counter);
   t.pool_slots = 1;
+  if (t.num_pairs) t.pair_desc = reinterpret_cast<int32_t*>(sc.ptr + o.pair_desc);
+  if (L->packed_faces) {
+    t.launch_rows = reinterpret_cast<int32_t*>(sc.ptr + o.launch_rows);
+    t.num_launch_rows = (int64_t)L->launch_rows.size();
+  }
   st = launch_attention(q, k, v, L, t, out, stream, false, false);
   if (st != CA_OK) sc.owner = 0;
   return st;

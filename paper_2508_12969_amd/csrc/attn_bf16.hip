@@ -17,7 +17,11 @@
 //
 // Pipeline.  One K buffer and one V buffer per workgroup: K(j+1) is fetched while the softmax and
 // the PV product of tile j run, V(j+1) while the next QK^T runs.
-#include "attn_bf16_common.h"
+//
+// Grids with a padded face (128-token tiles, head dim 128): the launch order then also holds the
+// workgroups that serve two packed query tiles (attn_bf16_pair_body.h); an entry below zero is the
+// complement of such a workgroup's index, and one launch runs both kinds, longest first.
+#include "attn_bf16_pair_body.h"
 
 namespace ca {
 namespace {
@@ -26,22 +30,10 @@ namespace {
 // tiles and the scatter of the output happen in the copies of this kernel instead of in separate
 // permutation passes.
 template <int B, int D, bool kNat>
-__global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
-void attn_bf16_kernel(AttnArgs a) {
+__device__ __forceinline__ void attn_row_body(const AttnArgs& a, int64_t row, int64_t batch, char* lds_k, char* lds_v) {
   using S = Shape<B, D>;
-  __shared__ __attribute__((aligned(1024))) char lds_k[S::kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char lds_v[S::kTileBytes];
-
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
-  const int64_t rows = (int64_t)a.num_heads * a.n;
-  __shared__ int pool_ticket;
-  const int64_t linear = launch_entry(a, &pool_ticket);
-  if (linear < 0) return;  // a surplus pool workgroup (all of its threads)
-  const int64_t item = linear % rows;
-  const int64_t batch = linear / rows;
-  const int64_t row = a.order ? a.order[item] : item;
   const int64_t head = row / a.n, q_tile = row - head * a.n;
   const int64_t plane = (batch * a.num_heads + head) * (kNat ? a.N_real * (int64_t)S::kRowBytes : a.n * (int64_t)S::kTileBytes);
   const char* Kp = static_cast<const char*>(a.k) + plane;
@@ -132,14 +124,37 @@ void attn_bf16_kernel(AttnArgs a) {
   w.store(static_cast<char*>(a.out) + plane + q_row * S::kRowBytes, qs.real, !kNat || qs.real);
 }
 
+// kPacked: the launch order may hold workgroups of two packed query tiles (entries below zero)
+template <int B, int D, bool kNat, bool kPacked>
+__global__ __attribute__((amdgpu_flat_work_group_size(B * 2, B * 2), amdgpu_waves_per_eu(2, 2)))
+void attn_bf16_kernel(AttnArgs a) {
+  using S = Shape<B, D>;
+  __shared__ __attribute__((aligned(1024))) char lds_k[S::kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_v[S::kTileBytes];
+  __shared__ int pool_ticket;
+  const int64_t linear = launch_entry(a, &pool_ticket);
+  if (linear < 0) return;  // a surplus pool workgroup (all of its threads)
+  const int64_t item = linear % a.entries;
+  const int64_t batch = linear / a.entries;
+  const int64_t entry = a.order ? a.order[item] : item;
+  if constexpr (kPacked) {
+    static_assert(B == 128 && D == 128, "packed query tiles exist for 128-token tiles with head dim 128");
+    if (entry < 0) {
+      attn_pair_body<128, kNat>(a, ~entry, batch, lds_k, lds_v);
+      return;
+    }
+  }
+  attn_row_body<B, D, kNat>(a, entry, batch, lds_k, lds_v);
+}
+
 template <int B, int D>
 hipError_t launch(const AttnArgs& a, hipStream_t stream) {
   const int64_t items = a.static_items + a.pool_wgs;
   if (a.natural) {
     if (a.tw % Shape<B, D>::kRowsPerLoad != 0) return hipErrorInvalidValue;  // a KiB block must stay inside one run
-    hipLaunchKernelGGL((attn_bf16_kernel<B, D, true>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<B, D, true, false>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
   } else {
-    hipLaunchKernelGGL((attn_bf16_kernel<B, D, false>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<B, D, false, false>), dim3((unsigned)items), dim3(B * 2), 0, stream, a);
   }
   return hipGetLastError();
 }
@@ -147,10 +162,17 @@ hipError_t launch(const AttnArgs& a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream) {
-  if (a.B == 64 && a.D == 128) return launch_attn_bf16_pair(a, stream);  // two query tiles per workgroup
-  const int64_t items = (int64_t)a.batch * a.num_heads * a.n;
+  const int64_t items = (int64_t)a.batch * a.entries;
   if (items == 0) return hipSuccess;
   if (a.static_items + a.pool_wgs > 0x7fffffff || a.static_items + a.pool_items != items) return hipErrorInvalidValue;
+  if (a.B == 128 && a.D == 128 && a.packed) {
+    if (!a.order || !a.pair_rows || !a.pair_desc) return hipErrorInvalidValue;
+    if (a.natural && a.tw % Shape<128, 128>::kRowsPerLoad != 0) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(a.static_items + a.pool_wgs)), block(256);
+    if (a.natural) hipLaunchKernelGGL((attn_bf16_kernel<128, 128, true, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((attn_bf16_kernel<128, 128, false, true>), grid, block, 0, stream, a);
+    return hipGetLastError();
+  }
   if (a.B == 128 && a.D == 128) return launch<128, 128>(a, stream);
   if (a.B == 128 && a.D == 64) return launch<128, 64>(a, stream);
   if (a.B == 64 && a.D == 64) return launch<64, 64>(a, stream);

@@ -28,9 +28,13 @@ struct AttnArgs {
   void* out;
   const int64_t* row_ptr;      // device; null selects the dense walk: every row uses col_meta[0..n)
   const int32_t* col_meta;     // device; per kept tile: tile id | padding class << 24; readable two words past the end
-  const int32_t* order;        // device; null = identity
+  const int32_t* order;        // device [entries]; the launch order: row ids; null = identity
+  int64_t entries;             // launch-order entries per batch entry (num_heads * n rows, or fewer entries when query tiles are packed)
+  int32_t packed;              // 1: `order` also holds workgroups of two packed query tiles, as the complement of their index in the pair tables
   const int32_t* pair_rows;    // device [2*num_pairs]; row ids of the two query tiles of a workgroup (-1: none), paired kernel only
   int64_t num_pairs;
+  const int32_t* pair_desc;    // device [num_pairs]; wave assignment of every workgroup of the paired kernel (layout.h)
+  uint64_t upper_empty_classes; // bit c: tiles of padding class c hold no token in the upper half of their slots (paired kernel, 128-token tiles)
   const int64_t* pair_walk_ptr; // device [num_pairs + 1]; null selects the dense walk: every pair uses pair_walk[0..n)
   const int32_t* pair_walk;     // device; per walked tile: tile id | padding class << 24 | kPairInFirst | kPairInSecond,
                                 // readable two words past the last entry
@@ -57,7 +61,8 @@ struct AttnArgs {
 hipError_t launch_attn_f32(const AttnArgs& a, hipStream_t stream);
 // bf16 problems, (B, D) in {64,128} x {64,128}
 hipError_t launch_attn_bf16(const AttnArgs& a, hipStream_t stream);
-// bf16 problems with B = 64, D = 128: two neighbouring query tiles per workgroup
+// bf16 problems with D = 128: workgroups that serve two query tiles (B = 64: every pair of neighbours; B = 128: the
+// packed tiles of the grid's padded faces)
 hipError_t launch_attn_bf16_pair(const AttnArgs& a, hipStream_t stream);
 
 struct MassArgs {

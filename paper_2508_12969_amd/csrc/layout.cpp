@@ -172,77 +172,44 @@ void build_order(ca_layout& L) {
 
 }  // namespace
 
-// Pairs of query tiles of one head for the kernel that gives two query tiles to a workgroup, in
-// launch order: pair_rows[2i], pair_rows[2i+1] are row ids head*n + tile, the second -1 for a single.
-static void build_pair_table(ca_layout& L) {
-  std::vector<int32_t>& pair_rows = L.pair_rows;
-  // Partner of a video tile: its neighbour along one grid axis (coordinates 2i and 2i+1; the last
-  // tile of an odd extent stays single).  Which axis costs the fewest walked tiles depends on the
-  // head's windows (a neighbour along an axis in which the windows are wide shares almost all of
-  // its list), so every head takes the axis with the smallest sum of union sizes.  Text tiles pair
-  // up in id order.
-  const int64_t n = L.n;
-  const int32_t ext[3] = {L.nT, L.nH, L.nW};
-  const int64_t stride[3] = {(int64_t)L.nH * L.nW, L.nW, 1};
-  auto union_size = [&](int64_t ra, int64_t rb) {
-    int64_t i = L.row_ptr[ra], ie = L.row_ptr[ra + 1], j = L.row_ptr[rb], je = L.row_ptr[rb + 1], m = 0;
-    while (i < ie && j < je) {
-      const int32_t ti = L.col_idx[i], tj = L.col_idx[j];
-      i += ti <= tj;
-      j += tj <= ti;
-      ++m;
-    }
-    return m + (ie - i) + (je - j);
-  };
-  auto for_pairs = [&](int axis, auto&& visit) {  // visit(tile_a, tile_b or -1) over the video tiles
-    for (int32_t t = 0; t < L.nT; ++t)
-      for (int32_t h = 0; h < L.nH; ++h)
-        for (int32_t w = 0; w < L.nW; ++w) {
-          const int32_t c[3] = {t, h, w};
-          if (c[axis] & 1) continue;
-          const int64_t id = ((int64_t)t * L.nH + h) * L.nW + w;
-          visit(id, c[axis] + 1 < ext[axis] ? id + stride[axis] : (int64_t)-1);
-        }
-  };
-  struct Pair {
-    int32_t a, b;
-    int64_t walked;
-  };
-  std::vector<Pair> pairs;
-  for (int32_t head = 0; head < L.prob.num_heads; ++head) {
-    const int64_t base = (int64_t)head * n;
-    // candidates: the axes with at least two tiles, tried in the order w, h, t; the first of the cheapest wins
-    int best_axis = 2;
-    int64_t best_cost = -1;
-    for (int axis = 2; axis >= 0; --axis) {
-      if (ext[axis] < 2) continue;
-      int64_t cost = 0;
-      for_pairs(axis, [&](int64_t a, int64_t b) {
-        cost += b < 0 ? L.row_ptr[base + a + 1] - L.row_ptr[base + a] : union_size(base + a, base + b);
-      });
-      if (best_cost < 0 || cost < best_cost) best_cost = cost, best_axis = axis;
-    }
-    for_pairs(best_axis, [&](int64_t a, int64_t b) {
-      const int64_t walked = b < 0 ? L.row_ptr[base + a + 1] - L.row_ptr[base + a] : union_size(base + a, base + b);
-      pairs.push_back({(int32_t)(base + a), b < 0 ? -1 : (int32_t)(base + b), walked});
-    });
-    for (int64_t a = L.n_vid; a < n; a += 2) {
-      const bool two = a + 1 < n;
-      const int64_t walked = two ? union_size(base + a, base + a + 1) : L.row_ptr[base + a + 1] - L.row_ptr[base + a];
-      pairs.push_back({(int32_t)(base + a), two ? (int32_t)(base + a + 1) : -1, walked});
-    }
+// A workgroup of the paired kernel: two rows of one head (b = -1: one), the assignment of its waves,
+// and the length of its walk (the union of the two rows).
+struct PairGroup {
+  int32_t a, b;
+  uint32_t desc;
+  int64_t walked;
+};
+
+static int64_t union_size(const ca_layout& L, int64_t ra, int64_t rb) {
+  if (rb < 0) return L.row_ptr[ra + 1] - L.row_ptr[ra];
+  int64_t i = L.row_ptr[ra], ie = L.row_ptr[ra + 1], j = L.row_ptr[rb], je = L.row_ptr[rb + 1], m = 0;
+  while (i < ie && j < je) {
+    const int32_t ti = L.col_idx[i], tj = L.col_idx[j];
+    i += ti <= tj;
+    j += tj <= ti;
+    ++m;
   }
-  // longest walks first, ties in the order built (head, then tile id)
-  std::stable_sort(pairs.begin(), pairs.end(), [](const Pair& x, const Pair& y) { return x.walked > y.walked; });
-  pair_rows.resize(2 * pairs.size());
-  for (size_t i = 0; i < pairs.size(); ++i) pair_rows[2 * i] = pairs[i].a, pair_rows[2 * i + 1] = pairs[i].b;
-  // The walk of a pair: the union of its two rows in ascending tile order, one word per tile:
-  // tile id | kPairInFirst if the first row keeps the tile | kPairInSecond if the second does.
-  L.pair_walk_ptr.assign(pairs.size() + 1, 0);
-  for (size_t i = 0; i < pairs.size(); ++i) L.pair_walk_ptr[i + 1] = L.pair_walk_ptr[i] + pairs[i].walked;
-  L.pair_walk.resize((size_t)L.pair_walk_ptr[pairs.size()]);
-  for (size_t p = 0; p < pairs.size(); ++p) {
-    const int64_t ra = pairs[p].a, rb = pairs[p].b;
+  return m + (ie - i) + (je - j);
+}
+
+// Launch order and walk lists of the paired kernel from its workgroups: longest walks first, ties
+// in the order built (head, then tile id); pair_rows[2i], pair_rows[2i+1] are row ids head*n + tile.
+// The walk of a workgroup is the union of its two rows in ascending tile order, one word per tile:
+// tile id | kPairInFirst if the first row keeps the tile | kPairInSecond if the second does.
+static void emit_pair_tables(ca_layout& L, std::vector<PairGroup>& groups) {
+  std::stable_sort(groups.begin(), groups.end(), [](const PairGroup& x, const PairGroup& y) { return x.walked > y.walked; });
+  L.pair_rows.resize(2 * groups.size());
+  L.pair_desc.resize(groups.size());
+  for (size_t i = 0; i < groups.size(); ++i) {
+    L.pair_rows[2 * i] = groups[i].a;
+    L.pair_rows[2 * i + 1] = groups[i].b;
+    L.pair_desc[i] = (int32_t)groups[i].desc;
+  }
+  L.pair_walk_ptr.assign(groups.size() + 1, 0);
+  for (size_t i = 0; i < groups.size(); ++i) L.pair_walk_ptr[i + 1] = L.pair_walk_ptr[i] + groups[i].walked;
+  L.pair_walk.resize((size_t)L.pair_walk_ptr[groups.size()]);
+  for (size_t p = 0; p < groups.size(); ++p) {
+    const int64_t ra = groups[p].a, rb = groups[p].b;
     int64_t i = L.row_ptr[ra], ie = L.row_ptr[ra + 1];
     int64_t j = rb < 0 ? 0 : L.row_ptr[rb], je = rb < 0 ? 0 : L.row_ptr[rb + 1];
     int64_t o = L.pair_walk_ptr[p];
@@ -254,6 +221,137 @@ static void build_pair_table(ca_layout& L) {
       j += tj == t;
     }
   }
+}
+
+// 64-token tiles: every query tile of a head is paired with a neighbour.
+static void build_pair_table(ca_layout& L) {
+  // Partner of a video tile: its neighbour along one grid axis (coordinates 2i and 2i+1; the last
+  // tile of an odd extent stays single).  Which axis costs the fewest walked tiles depends on the
+  // head's windows (a neighbour along an axis in which the windows are wide shares almost all of
+  // its list), so every head takes the axis with the smallest sum of union sizes.  Text tiles pair
+  // up in id order.
+  const int64_t n = L.n;
+  const int32_t ext[3] = {L.nT, L.nH, L.nW};
+  const int64_t stride[3] = {(int64_t)L.nH * L.nW, L.nW, 1};
+  auto for_pairs = [&](int axis, auto&& visit) {  // visit(tile_a, tile_b or -1) over the video tiles
+    for (int32_t t = 0; t < L.nT; ++t)
+      for (int32_t h = 0; h < L.nH; ++h)
+        for (int32_t w = 0; w < L.nW; ++w) {
+          const int32_t c[3] = {t, h, w};
+          if (c[axis] & 1) continue;
+          const int64_t id = ((int64_t)t * L.nH + h) * L.nW + w;
+          visit(id, c[axis] + 1 < ext[axis] ? id + stride[axis] : (int64_t)-1);
+        }
+  };
+  std::vector<PairGroup> groups;
+  for (int32_t head = 0; head < L.prob.num_heads; ++head) {
+    const int64_t base = (int64_t)head * n;
+    // candidates: the axes with at least two tiles, tried in the order w, h, t; the first of the cheapest wins
+    int best_axis = 2;
+    int64_t best_cost = -1;
+    for (int axis = 2; axis >= 0; --axis) {
+      if (ext[axis] < 2) continue;
+      int64_t cost = 0;
+      for_pairs(axis, [&](int64_t a, int64_t b) { cost += union_size(L, base + a, b < 0 ? -1 : base + b); });
+      if (best_cost < 0 || cost < best_cost) best_cost = cost, best_axis = axis;
+    }
+    constexpr uint32_t kSingle = pair_desc_wave(0, 0, 0) | pair_desc_wave(1, 0, 1);  // a tile without a partner
+    for_pairs(best_axis, [&](int64_t a, int64_t b) {
+      const int64_t rb = b < 0 ? -1 : base + b;
+      groups.push_back({(int32_t)(base + a), (int32_t)rb, rb < 0 ? kSingle : kPairPlain, union_size(L, base + a, rb)});
+    });
+    for (int64_t a = L.n_vid; a < n; a += 2) {
+      const int64_t rb = a + 1 < n ? base + a + 1 : -1;
+      groups.push_back({(int32_t)(base + a), (int32_t)rb, rb < 0 ? kSingle : kPairPlain, union_size(L, base + a, rb)});
+    }
+  }
+  emit_pair_tables(L, groups);
+}
+
+// 128-token tiles: a query tile on a padded face of the grid holds tokens for one to three waves
+// only (its slots are handed to lanes token-holding slots first), and in a workgroup of its own the
+// other waves idle while the workgroup still pays for the tile copies and the barriers of every
+// step.  Such tiles are packed along w, inside one row of tiles of the grid: their waves fill
+// workgroups of four in order, a tile's waves may continue in the next workgroup, and a workgroup
+// serves at most two tiles (it walks the union of their rows).  A head is packed only if that is
+// cheaper by the measured cost of a tile step with 1, 2, 3 or 4 working waves (65, 73, 88, 100):
+// neighbours with narrow windows share too little of their lists.  launch_rows is then the launch
+// order of both kinds of workgroup: the rows that keep a workgroup of their own and the packed ones.
+static void build_packed_faces(ca_layout& L) {
+  const int64_t n = L.n;
+  static const int64_t kStepCost[5] = {0, 65, 73, 88, 100};
+  std::vector<int32_t> waves(n, 4);
+  bool any = false;
+  for (int64_t t = 0; t < L.n_vid; ++t) {
+    const SlotMask& m = L.class_mask[L.tile_class[t]];
+    const int valid = __builtin_popcount(m.w[0]) + __builtin_popcount(m.w[1]) + __builtin_popcount(m.w[2]) + __builtin_popcount(m.w[3]);
+    waves[t] = (valid + 31) / 32;
+    any = any || waves[t] < 4;
+  }
+  L.packed_faces = false;
+  L.launch_rows.clear();
+  if (!any) return;
+  std::vector<PairGroup> groups, head_groups;
+  std::vector<char> packed((size_t)L.prob.num_heads * n, 0);
+  for (int32_t head = 0; head < L.prob.num_heads; ++head) {
+    const int64_t base = (int64_t)head * n;
+    head_groups.clear();
+    int64_t plain_cost = 0;
+    for (int32_t kt = 0; kt < L.nT; ++kt)
+      for (int32_t kh = 0; kh < L.nH; ++kh) {
+        PairGroup cur{-1, -1, 0, 0};
+        int used = 0;
+        auto flush = [&]() {
+          if (used) head_groups.push_back(cur);
+          cur = PairGroup{-1, -1, 0, 0};
+          used = 0;
+        };
+        for (int32_t kw = 0; kw < L.nW; ++kw) {
+          const int64_t t = ((int64_t)kt * L.nH + kh) * L.nW + kw;
+          if (waves[t] >= 4) {
+            flush();
+            continue;
+          }
+          plain_cost += (L.row_ptr[base + t + 1] - L.row_ptr[base + t]) * kStepCost[waves[t]];
+          for (int first = 0; first < waves[t];) {
+            if (used == 4 || (cur.b >= 0 && cur.b != base + t)) flush();
+            int second = 0;
+            if (cur.a < 0) cur.a = (int32_t)(base + t);
+            else if (cur.a != base + t) cur.b = (int32_t)(base + t), second = 1;
+            const int take = std::min(waves[t] - first, 4 - used);
+            for (int i = 0; i < take; ++i) cur.desc |= pair_desc_wave(used + i, second, first + i);
+            used += take;
+            first += take;
+          }
+        }
+        flush();
+      }
+    int64_t packed_cost = 0;
+    for (PairGroup& g : head_groups) {
+      g.walked = union_size(L, g.a, g.b);
+      packed_cost += g.walked * kStepCost[__builtin_popcount((g.desc >> 4) & 0xFu)];
+    }
+    if (head_groups.empty() || packed_cost >= plain_cost) continue;
+    for (const PairGroup& g : head_groups) {
+      packed[g.a] = 1;
+      if (g.b >= 0) packed[g.b] = 1;
+      groups.push_back(g);
+    }
+  }
+  if (groups.empty()) return;
+  emit_pair_tables(L, groups);
+  L.packed_faces = true;
+  // one launch order for both kinds of workgroup, longest first: a row id, or the complement of a
+  // packed workgroup's index (ties: the packed workgroup first)
+  L.launch_rows.reserve(L.order.size());
+  size_t g = 0;
+  for (int32_t r : L.order) {
+    if (packed[r]) continue;
+    const int64_t len = L.row_ptr[r + 1] - L.row_ptr[r];
+    while (g < groups.size() && groups[g].walked >= len) L.launch_rows.push_back(~(int32_t)g++);
+    L.launch_rows.push_back(r);
+  }
+  while (g < groups.size()) L.launch_rows.push_back(~(int32_t)g++);
 }
 
 // The XCDs of one card do not run at the same speed (measured: up to 5 % apart in finishing time on
@@ -284,15 +382,19 @@ LaunchSplit split_launch(const int64_t* work, int64_t entries) {
 
 namespace {
 void build_launch_splits(ca_layout& L) {
-  const int64_t rows = (int64_t)L.prob.num_heads * L.n;
+  const std::vector<int32_t>& launched = L.packed_faces ? L.launch_rows : L.order;
+  const int64_t rows = (int64_t)launched.size();
   std::vector<int64_t> work(rows);
-  for (int64_t i = 0; i < rows; ++i) work[i] = L.row_ptr[L.order[i] + 1] - L.row_ptr[L.order[i]];
+  for (int64_t i = 0; i < rows; ++i) {
+    const int32_t e = launched[i];
+    work[i] = e < 0 ? L.pair_walk_ptr[~e + 1] - L.pair_walk_ptr[~e] : L.row_ptr[e + 1] - L.row_ptr[e];
+  }
   L.split_rows = split_launch(work.data(), rows);
   std::fill(work.begin(), work.end(), L.n);
   L.split_rows_dense = split_launch(work.data(), rows);
   const int64_t pairs = (int64_t)L.pair_rows.size() / 2;
   L.split_pairs = L.split_pairs_dense = LaunchSplit{};
-  if (pairs) {
+  if (pairs && !L.packed_faces) {
     work.resize(pairs);
     for (int64_t i = 0; i < pairs; ++i) work[i] = L.pair_walk_ptr[i + 1] - L.pair_walk_ptr[i];
     L.split_pairs = split_launch(work.data(), pairs);
@@ -314,9 +416,13 @@ void finish_host_tables(ca_layout& L) {
   build_order(L);
   build_slot_masks(L);
   L.pair_rows.clear();
+  L.pair_desc.clear();
   L.pair_walk_ptr.clear();
   L.pair_walk.clear();
+  L.packed_faces = false;
+  L.launch_rows.clear();
   if (L.prob.dtype == CA_BF16 && L.B == 64 && L.prob.head_dim == 128) build_pair_table(L);
+  if (L.prob.dtype == CA_BF16 && L.B == 128 && L.prob.head_dim == 128) build_packed_faces(L);
   build_launch_splits(L);
 }
 

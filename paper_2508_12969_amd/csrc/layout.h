@@ -14,6 +14,16 @@ namespace ca {
 // Membership bits of a walk word of the paired kernel (bits 30 and 31; the tile id is below bit 24).
 constexpr uint32_t kPairInFirst = 1u << 30, kPairInSecond = 1u << 31;
 
+// How the four waves of a workgroup of the paired kernel are assigned (one word per workgroup):
+// bit w: wave w works for the second query tile of the pair (else the first); bit 4 + w: wave w has
+// queries at all; bits 8 + 4w .. 11 + 4w: the wave's first query slot / 32, counted in the tile's
+// token-holding-slots-first order.  The plain pair of two 64-token tiles is kPairPlain: waves 0-1 hold
+// slots 0-63 of the first tile, waves 2-3 those of the second.
+constexpr uint32_t kPairPlain = 0xCu | 0xF0u | (0x1010u << 8);
+constexpr uint32_t pair_desc_wave(int wave, int second, int first_slot32) {
+  return ((uint32_t)second << wave) | (1u << (4 + wave)) | ((uint32_t)first_slot32 << (8 + 4 * wave));
+}
+
 // Validity of the B token slots of a tile, one bit per slot (B <= 128).
 struct SlotMask {
   uint32_t w[4];
@@ -36,6 +46,9 @@ struct DeviceTables {
   int32_t* col_meta = nullptr;   // [nnz] kept key tiles, ascending inside each row: tile id | class << 24
   int32_t* dense_meta = nullptr; // [n] the same packing for the list 0..n-1 (dense walk)
   int32_t* order = nullptr;      // [num_heads*n] launch order of row ids head*n + tile
+  int32_t* launch_rows = nullptr; // [num_launch_rows] launch order when query tiles are packed (row ids, and ~i for packed workgroup i); else null: `order`
+  int64_t num_launch_rows = 0;
+  int32_t* pair_desc = nullptr;  // [num_pairs] wave assignment of every workgroup of the paired kernel
   int32_t* pair_rows = nullptr;  // [2*num_pairs] row ids of the two query tiles a workgroup of the paired kernel owns (-1: none), in launch order
   int64_t num_pairs = 0;
   int64_t* pair_walk_ptr = nullptr;   // [num_pairs + 1]
@@ -65,7 +78,14 @@ struct ca_layout {
   std::vector<int32_t> col_idx;             // [nnz]
   std::vector<std::vector<int64_t>> head_row_ptr;  // per head, relative offsets (C-ABI view)
   std::vector<int32_t> order;               // [num_heads*n]
-  std::vector<int32_t> pair_rows;           // [2*num_pairs], empty unless the paired kernel serves this layout
+  std::vector<int32_t> pair_rows;           // [2*num_pairs], empty unless the paired kernel serves (part of) this layout
+  std::vector<int32_t> pair_desc;           // [num_pairs] wave assignment (kPairPlain for a plain pair)
+  // 128-token tiles, head dim 128: query tiles whose tokens fill fewer than four waves (tiles on a
+  // padded face of the grid) are packed several to a workgroup (pair_rows, pair_desc), and
+  // `launch_rows` is the launch order of everything, longest first: `order` without the packed
+  // rows, and the complement ~i of packed workgroup i.
+  bool packed_faces = false;
+  std::vector<int32_t> launch_rows;
   std::vector<int64_t> pair_walk_ptr;       // [num_pairs + 1] offsets into pair_walk
   std::vector<int32_t> pair_walk;           // per pair: union of its two rows, tile id | kPairInFirst | kPairInSecond
   std::vector<int32_t> tile_class;          // [n]
@@ -89,7 +109,7 @@ struct ca_layout {
   std::vector<unsigned char> static_image;
   struct StaticOffsets {
     size_t row_ptr = 0, col_meta = 0, order = 0, pair_rows = 0, pair_walk_ptr = 0, pair_walk = 0, tile_class = 0,
-           class_mask = 0, class_perm = 0, pool_counter = 0;
+           class_mask = 0, class_perm = 0, pool_counter = 0, pair_desc = 0, launch_rows = 0;
   } static_off;
 };
 

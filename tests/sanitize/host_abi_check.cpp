@@ -114,20 +114,97 @@ void check_split(const ca::LaunchSplit& sp, const std::vector<int64_t>& work) {
 }
 
 void check_layout_splits(const ca_layout* L) {
-  const int64_t rows = (int64_t)L->prob.num_heads * L->n;
+  const std::vector<int32_t>& launched = L->packed_faces ? L->launch_rows : L->order;
+  const int64_t rows = (int64_t)launched.size();
   std::vector<int64_t> work(rows);
-  for (int64_t i = 0; i < rows; ++i) work[i] = L->row_ptr[L->order[i] + 1] - L->row_ptr[L->order[i]];
+  for (int64_t i = 0; i < rows; ++i) {
+    const int32_t e = launched[i];  // a row, or the complement of a packed workgroup's index
+    work[i] = e < 0 ? L->pair_walk_ptr[~e + 1] - L->pair_walk_ptr[~e] : L->row_ptr[e + 1] - L->row_ptr[e];
+  }
   for (int64_t i = 1; i < rows; ++i) CHECK(work[i] <= work[i - 1]);  // the launch order is by descending length
   check_split(L->split_rows, work);
   check_split(L->split_rows_dense, std::vector<int64_t>(rows, L->n));
   const int64_t pairs = (int64_t)L->pair_rows.size() / 2;
-  if (pairs) {
+  if (pairs && !L->packed_faces) {
     work.assign(pairs, 0);
     for (int64_t i = 0; i < pairs; ++i) work[i] = L->pair_walk_ptr[i + 1] - L->pair_walk_ptr[i];
     check_split(L->split_pairs, work);
     check_split(L->split_pairs_dense, std::vector<int64_t>(pairs, L->n));
   } else {
     CHECK(L->split_pairs.pool_entries == 0 && L->split_pairs_dense.pool_entries == 0);
+  }
+}
+
+// Who computes which queries: every 32-query wave slot of every row that holds a token belongs to
+// exactly one wave, either of the row's own workgroup (launch_rows: all four) or of a workgroup of
+// two query tiles (pair_desc); walks are unions of the two rows with the right membership bits.
+void check_wave_assignment(const ca_layout* L) {
+  const int64_t rows = (int64_t)L->prob.num_heads * L->n;
+  const int64_t pairs = (int64_t)L->pair_rows.size() / 2;
+  CHECK(L->pair_desc.size() == (size_t)pairs);
+  if (!pairs) {
+    CHECK(!L->packed_faces && L->launch_rows.empty());
+    return;
+  }
+  const int slots = (int)((L->B + 31) / 32);
+  std::vector<int> owners((size_t)rows * 4, 0);
+  if (L->packed_faces) {
+    // launch_rows: `order` without the packed rows, in the same order, and every packed workgroup once
+    std::vector<char> own(rows, 0);
+    std::vector<int32_t> kept_rows;
+    std::vector<int> seen_group(pairs, 0);
+    for (int32_t e : L->launch_rows) {
+      if (e >= 0) kept_rows.push_back(e);
+      else if (~e < pairs) seen_group[~e]++;
+      else CHECK(false);
+    }
+    for (int64_t g = 0; g < pairs; ++g) CHECK(seen_group[g] == 1);
+    size_t at = 0;
+    for (int32_t r : L->order)
+      if (at < kept_rows.size() && kept_rows[at] == r) own[r] = 1, ++at;
+    CHECK(at == kept_rows.size());
+    for (int64_t r = 0; r < rows; ++r)
+      if (own[r]) for (int w = 0; w < slots; ++w) owners[r * 4 + w]++;
+  }
+  for (int64_t p = 0; p < pairs; ++p) {
+    const int32_t a = L->pair_rows[2 * p], b = L->pair_rows[2 * p + 1];
+    const uint32_t desc = (uint32_t)L->pair_desc[p];
+    CHECK(a >= 0 && a < rows && b < rows && a != b);
+    if (b >= 0) CHECK(a / L->n == b / L->n);
+    for (int w = 0; w < 4; ++w) {
+      if (!((desc >> (4 + w)) & 1u)) continue;
+      const int second = (desc >> w) & 1u, first = (desc >> (8 + 4 * w)) & 0xFu;
+      CHECK(first < 4);
+      if (second) CHECK(b >= 0);
+      const int64_t r = second ? b : a;
+      if (r >= 0 && first < 4) owners[r * 4 + first]++;
+    }
+    if (p > 0) CHECK(L->pair_walk_ptr[p + 1] - L->pair_walk_ptr[p] <= L->pair_walk_ptr[p] - L->pair_walk_ptr[p - 1]);
+    // the walk: ascending tile ids, each kept by at least one of the two rows, bits as the rows say
+    std::vector<char> in_a(L->n, 0), in_b(L->n, 0);
+    for (int64_t i = L->row_ptr[a]; i < L->row_ptr[a + 1]; ++i) in_a[L->col_idx[i]] = 1;
+    if (b >= 0) for (int64_t i = L->row_ptr[b]; i < L->row_ptr[b + 1]; ++i) in_b[L->col_idx[i]] = 1;
+    int64_t members = 0;
+    int32_t last = -1;
+    for (int64_t i = L->pair_walk_ptr[p]; i < L->pair_walk_ptr[p + 1]; ++i) {
+      const uint32_t word = (uint32_t)L->pair_walk[i];
+      const int32_t t = (int32_t)(word & 0xffffffu);
+      CHECK(t > last && t < L->n);
+      last = t;
+      CHECK(((word >> 30) & 1u) == (uint32_t)in_a[t] && (word >> 31) == (uint32_t)in_b[t]);
+      CHECK(in_a[t] || in_b[t]);
+      members += in_a[t] + in_b[t];
+    }
+    CHECK(members == (L->row_ptr[a + 1] - L->row_ptr[a]) + (b >= 0 ? L->row_ptr[b + 1] - L->row_ptr[b] : 0));
+  }
+  for (int64_t r = 0; r < rows; ++r) {
+    const ca::SlotMask& m = L->class_mask[L->tile_class[r % L->n]];
+    const int valid = __builtin_popcount(m.w[0]) + __builtin_popcount(m.w[1]) + __builtin_popcount(m.w[2]) + __builtin_popcount(m.w[3]);
+    for (int w = 0; w < 4; ++w) {
+      const bool holds_tokens = w * 32 < valid;
+      if (holds_tokens) CHECK(owners[r * 4 + w] == 1);
+      else CHECK(owners[r * 4 + w] <= 1);
+    }
   }
 }
 
@@ -195,6 +272,7 @@ void run_case(std::mt19937& rng, ca_problem p) {
   check_layout_views(L, p);
   check_packing(L);
   check_layout_splits(L);
+  check_wave_assignment(L);
 
   // round trip through the CSR import, then union with a second random layout and similarity
   int64_t n = 0;
@@ -213,6 +291,7 @@ void run_case(std::mt19937& rng, ca_problem p) {
     check_layout_views(merged, p);
     check_packing(merged);
     check_layout_splits(merged);
+    check_wave_assignment(merged);
     double sim = -1;
     CHECK(compact_attn_layout_similarity(merged, 0, merged, 0, &sim) == CA_OK && sim == 1.0);
     CHECK(compact_attn_layout_similarity(L, 0, other, p.num_heads - 1, &sim) == CA_OK && sim >= 0.0 && sim <= 1.0);

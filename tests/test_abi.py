@@ -403,6 +403,89 @@ def _check_pairs(lay, g, masks):
     assert not np.any(words & 0x3F000000)
 
 
+def _check_wave_assignment(lay, g, masks):
+    """Every 32-query wave slot of every row that holds a token belongs to exactly one wave of one
+    workgroup: the row's own (launch_rows, four waves) or a workgroup of two packed query tiles."""
+    pairs, walk_ptr, walk = ca.compact_attn_layout_pairs(lay)
+    desc, launch = ca.compact_attn_layout_packing(lay)
+    Hd, n = masks.shape[0], g.n
+    valid = np.bincount(g.token_slots() // g.B, minlength=n)
+    owners = np.zeros((Hd * n, 4), dtype=int)
+    rows_kept = launch[launch >= 0]
+    for r in rows_kept:
+        owners[r, :] += 1
+    groups_seen = np.sort(~launch[launch < 0])
+    assert np.array_equal(groups_seen, np.arange(len(pairs)))
+    order = ca.compact_attn_layout_order(lay)
+    assert np.array_equal(rows_kept, order[np.isin(order, rows_kept)])        # same relative order as the full launch order
+    counts = masks.reshape(Hd * n, n).sum(axis=1)
+    lengths = np.array([counts[e] if e >= 0 else walk_ptr[~e + 1] - walk_ptr[~e] for e in launch])
+    assert np.all(np.diff(lengths) <= 0)                                      # longest first
+    words = walk.view(np.uint32)
+    for i, (a, b) in enumerate(pairs):
+        assert a >= 0 and a != b and (b < 0 or a // n == b // n)
+        d = int(desc[i])
+        for w in range(4):
+            if not (d >> (4 + w)) & 1:
+                continue
+            second, first = (d >> w) & 1, (d >> (8 + 4 * w)) & 0xF
+            assert first < 4 and (not second or b >= 0)
+            owners[b if second else a, first] += 1
+        seg = words[walk_ptr[i]:walk_ptr[i + 1]]
+        ma = masks.reshape(Hd * n, n)[a]
+        mb = masks.reshape(Hd * n, n)[b] if b >= 0 else np.zeros(n, dtype=bool)
+        assert np.array_equal(seg & 0xFFFFFF, np.flatnonzero(ma | mb))
+        assert np.array_equal((seg >> 30) & 1, ma[ma | mb]) and np.array_equal(seg >> 31, mb[ma | mb])
+    for r in range(Hd * n):
+        need = -(-int(valid[r % n]) // 32)
+        assert np.all(owners[r, :need] == 1) and np.all(owners[r, need:] <= 1), (r, owners[r], need)
+
+
+def test_packed_face_tiles_hand_worked():
+    """128-token tiles (2x8x8) on a 3 x 13 x 16 grid: 2 x 2 x 2 tiles.  Tiles 0, 1 are full; 2, 3 (last
+    tile row: 5 of 8 rows) hold 80 tokens = three waves; 4..7 (last tile frame: 1 of 2 frames) hold 64
+    or 40 tokens = two waves.  With a head that keeps every tile, packing along w gives, in the order
+    built: [tile 2: waves 0-2 | tile 3: wave 3], [tile 3: its other two waves], [4 | 5], [6 | 7]; all
+    walks have the same length, so these four come first in the launch order, then rows 0 and 1."""
+    T, H, W, tile = 3, 13, 16, (2, 8, 8)
+    g = Geometry(T, H, W, *tile, 0)
+    heads = [[(9, (9, 9), ABSENT)]]
+    lay = ca.compact_attn_build_layout(T, H, W, tile, 0, 1, 1, 128, "bf16", heads)
+    pairs, walk_ptr, walk = ca.compact_attn_layout_pairs(lay)
+    desc, launch = ca.compact_attn_layout_packing(lay)
+    assert pairs.tolist() == [[2, 3], [3, -1], [4, 5], [6, 7]]
+    wave = lambda w, second, first: (second << w) | (1 << (4 + w)) | (first << (8 + 4 * w))
+    assert desc.tolist() == [wave(0, 0, 0) | wave(1, 0, 1) | wave(2, 0, 2) | wave(3, 1, 0),
+                             wave(0, 0, 1) | wave(1, 0, 2),
+                             wave(0, 0, 0) | wave(1, 0, 1) | wave(2, 1, 0) | wave(3, 1, 1),
+                             wave(0, 0, 0) | wave(1, 0, 1) | wave(2, 1, 0) | wave(3, 1, 1)]
+    assert launch.tolist() == [~0, ~1, ~2, ~3, 0, 1]
+    assert np.array_equal(walk_ptr, np.arange(5) * 8)
+    masks = np.stack([OL.mask_of_csr(g.n, *csr) for csr in OL.build_csr(g, heads)])
+    _check_wave_assignment(lay, g, masks)
+    lay.free()
+    # a head whose windows are one tile wide shares nothing between neighbours along w: not packed
+    lay = ca.compact_attn_build_layout(T, H, W, tile, 0, 1, 1, 128, "bf16", [[(9, (9, 0), ABSENT)]])
+    assert ca.compact_attn_layout_pairs(lay)[0].shape == (0, 2)
+    desc, launch = ca.compact_attn_layout_packing(lay)
+    assert len(desc) == 0 and np.array_equal(launch, ca.compact_attn_layout_order(lay))
+    lay.free()
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.integers(1, 7), st.integers(3, 40), st.integers(3, 40), st.sampled_from([(2, 8, 8), (1, 8, 16), (4, 4, 8)]),
+       st.integers(0, 2), st.lists(st.tuples(st.integers(0, 3), _win, _win), min_size=1, max_size=3), st.integers(0, 10 ** 6))
+def test_packed_face_tiles_cover_every_query_once(T, H, W, tile, n_txt, groups, seed):
+    rng = np.random.default_rng(seed)
+    heads = [sorted({dt: (dt, a, b) for dt, a, b in groups}.values()), [(9, (9, 9), ABSENT)],
+             [(int(rng.integers(0, 3)), (int(rng.integers(0, 3)), 9), ABSENT)]]
+    g = Geometry(T, H, W, *tile, n_txt * 128)
+    lay = ca.compact_attn_build_layout(T, H, W, tile, n_txt * 128, 1, len(heads), 128, "bf16", heads)
+    masks = np.stack([OL.mask_of_csr(g.n, *csr) for csr in OL.build_csr(g, heads)])
+    _check_wave_assignment(lay, g, masks)
+    lay.free()
+
+
 def test_pair_table_of_config3_heads_and_absent_elsewhere():
     wl = get_workload("cfg3")
     g = geometry_of(wl)
