@@ -27,8 +27,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # so the figure is a recorded measurement, not one taken live: it is printed with the summary file
 # it comes from, and as null for a workload without a committed counter run.
 RECORDED_TRAFFIC = {
-    "cfg4-S65": {"bytes": 140.9e9, "source": "profiles/attn_bf16_kernel_cfg4-S65_pmc.md"},
-    "cfg3": {"bytes": 60.6e9, "source": "profiles/attn_bf16_pair_kernel_cfg3.md"},
+    "cfg4-S65": {"bytes": 113.8e9, "source": "profiles/attn_bf16_kernel_cfg4-S65_pmc.md"},
+    "cfg3": {"bytes": 60.3e9, "source": "profiles/attn_bf16_pair_kernel_cfg3.md"},
 }
 OTHER_CONFIGS = ("cfg4-S50", "cfg4-S80", "cfg3", "cfg5")
 
