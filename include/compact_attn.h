@@ -144,7 +144,10 @@ int compact_attn_layout_info(const ca_layout* layout, int64_t* n_tiles, int64_t*
 int compact_attn_layout_csr(const ca_layout* layout, int32_t head, const int64_t** row_ptr,
                             const int32_t** col_idx);
 
-/* Host view of the launch order: int32[num_heads*n] of row ids head*n + query_tile. */
+/* Host view of the work ordering of all rows: int32[num_heads*n] of row ids head*n + query_tile by
+ * descending number of kept key tiles, ties by ascending row id.  It is the launch order of the
+ * kernels that give every row a workgroup of its own; where two query tiles share a workgroup see
+ * compact_attn_layout_pairs and compact_attn_layout_packing. */
 int compact_attn_layout_order(const ca_layout* layout, const int32_t** order);
 
 /* Host view of the workgroups that serve two query tiles (work ordering of Appendix D's block loop
