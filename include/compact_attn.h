@@ -25,8 +25,11 @@
  *     `stream` is being captured at that moment).
  *   - A layout may be used by compute calls on several streams at once; launches of 4096 rows and
  *     more keep a ticket counter in the layout's device tables while they run, one of 64 taken
- *     round-robin, so at most 64 such launches of one layout may be in flight on different
- *     streams at a time (launches on one stream run one after the other and never conflict).
+ *     round-robin at the call, so at most 64 such launches of one layout may be in flight on
+ *     different streams at a time (launches on one stream run one after the other and never
+ *     conflict).  A call captured into a HIP graph keeps the counter it was given: replays of that
+ *     graph must not overlap in time with other launches of the same layout on other streams
+ *     (build a second layout for those).
  *   - Failures detected on the host leave all outputs untouched.
  *
  * Tile arithmetic (Sec. 4.1, space-time tiles; Sec. 3.1 / Appendix D, tile-order flattening)
